@@ -1,0 +1,196 @@
+/*
+ * vlcache.h -- C ABI of the VL-Cache hot path for AMD MI355X (gfx950).
+ *
+ * The path runs once after prefill (score -> sparsity -> allocate -> topk_compact) and then
+ * on every decode step (decode_attn over the compressed, ragged, per-layer cache).
+ *
+ * Notation is the paper's: m prompt tokens, tau rows of the post-vision query window
+ * (the last tau prompt tokens), L layers, Hq query heads, Hkv key/value heads,
+ * g = Hq / Hkv, d head dimension, p the ThresholdFilter threshold, alpha the whole-model
+ * cache budget, k_l the token budget of layer l.
+ *
+ * Conventions shared by every call
+ *   - Tensor arguments are DEVICE pointers owned by the caller, contiguous (row-major) in
+ *     the stated layout, 16-byte aligned.  The library keeps no pointer after a call returns,
+ *     except for the arena handed to vlc_cache_create.
+ *   - Every call only enqueues work on the given HIP stream and returns; no call
+ *     synchronises, allocates or frees device memory (vlc_cache_status synchronises, and says so).
+ *   - Calls return a vlc_status; nothing throws or aborts.  vlc_last_error_string() holds a
+ *     description of the calling thread's last failure.
+ *   - Errors that only the device can see (a budget outside [1, m], a cache arena too
+ *     small for the budgets) set a sticky flag inside the cache; the offending rows are skipped
+ *     without touching memory, and vlc_cache_status reports the flag.
+ *   - Query head h reads key/value head h / g (consecutive query heads share a KV head).
+ */
+#ifndef VLCACHE_H
+#define VLCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VLC_OK = 0,
+    VLC_ERR_INVALID_ARG = 1,   /* null pointer, value out of range, inconsistent call order */
+    VLC_ERR_SHAPE = 2,         /* shape the kernels do not cover (see vlc_shape)             */
+    VLC_ERR_DTYPE = 3,
+    VLC_ERR_CAPACITY = 4,      /* arena / workspace too small, or more appends than reserved  */
+    VLC_ERR_HIP = 5,           /* a HIP runtime call failed (message in vlc_last_error_string)*/
+    VLC_ERR_UNIMPLEMENTED = 6
+} vlc_status;
+
+typedef enum { VLC_F32 = 0, VLC_BF16 = 1 } vlc_dtype;
+
+/* A hipStream_t, passed as a plain pointer so that C callers need no HIP headers.
+ * NULL is the device's default stream. */
+typedef void* vlc_stream;
+
+/* Problem shape, uniform over the batch (every request has the same m and tau).
+ * Supported: d in {64, 128}; Hq % Hkv == 0 with g <= 8; 1 <= tau <= m; g * tau <= 512;
+ * L <= 1024; dtype is the storage type of Q, K, V and of the decode output. */
+typedef struct {
+    int32_t B, L, Hq, Hkv, d, m, tau;
+    int32_t dtype;             /* vlc_dtype */
+} vlc_shape;
+
+const char* vlc_last_error_string(void);
+const char* vlc_version(void);
+
+/* Bytes of scratch vlc_score / vlc_sparsity need for this shape (partial row statistics). */
+size_t vlc_workspace_bytes(const vlc_shape* shape);
+
+/*
+ * vlc_score -- accumulated post-vision attention (paper Sec. 3.2; Alg. 1 ComputeSparsity for
+ * the softmax; App. A.3 for the two-sweep schedule that never writes the attention matrix).
+ *
+ *   s_ij  = sm_scale[l] * <q_win[b,l,h,i,:], k[b,l,h/g,j,:]>,  valid iff j <= m - tau + i
+ *   A'_ij = exp(s_ij - M_i) / Z_i over the valid j of row i   (M_i = row max, Z_i = row sum)
+ *   scores[b,l,hkv,j] = sum over the g query heads of the group and over rows i of A'_ij
+ *   nnz[b,l,h]        = #{valid (i,j): s_ij - M_i >= ln p}     (only if nnz != NULL; Eq. 1)
+ *
+ * q_win   [B,L,Hq,tau,d]  in   storage dtype
+ * k       [B,L,Hkv,m,d]   in   storage dtype
+ * sm_scale[L] float       in   per-layer logit scale, or NULL for 1/sqrt(d)
+ * p                       in   threshold in (0,1); ignored when nnz == NULL
+ * scores  [B,L,Hkv,m]     out  fp32
+ * row_max [B,L,Hq,tau]    out  fp32, M_i (natural-log domain)
+ * row_sum [B,L,Hq,tau]    out  fp32, Z_i
+ * nnz     [B,L,Hq]        out  uint64, may be NULL (counting rides on the score sweep)
+ * workspace               scratch of at least vlc_workspace_bytes(shape) bytes
+ */
+vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k,
+                     const float* sm_scale, float p,
+                     float* scores, float* row_max, float* row_sum, uint64_t* nnz,
+                     void* workspace, size_t workspace_bytes, vlc_stream stream);
+
+/*
+ * vlc_sparsity -- ThresholdFilter sparsity of the post-vision attention (paper Eq. 1, Eq. 2,
+ * Alg. 1 ComputeSparsity):  gamma = 1 - nnz / D,  D = tau (m - tau) + tau (tau + 1) / 2.
+ *
+ * Two modes:
+ *   q_win != NULL: standalone sweep.  Counts nnz as defined under vlc_score; row_max may be
+ *                  the array vlc_score produced, or NULL to recompute the row statistics.
+ *   q_win == NULL: finalise only.  nnz is an INPUT (as filled by vlc_score) and gamma is
+ *                  computed from it; k, sm_scale, row_max and workspace are ignored.
+ * nnz   [B,L,Hq] uint64   out (in, when finalising)
+ * gamma [B,L,Hq] float    out, may be NULL
+ */
+vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k,
+                        const float* sm_scale, const float* row_max, float p,
+                        uint64_t* nnz, float* gamma,
+                        void* workspace, size_t workspace_bytes, vlc_stream stream);
+
+/*
+ * vlc_allocate -- sparsity-aware layer budgets (paper Alg. 1, SkewedCacheBudgetAllocation),
+ * in integers.  Per request: n_l = sum_h nnz[b,l,h] (proportional to 1 - gamma'_l),
+ * N = sum_l n_l, B_tot = floor(alpha_num * L * m / alpha_den); floor quotas
+ * q_l = floor(n_l * B_tot / N), then +1 to the B_tot - sum q_l layers with the largest
+ * remainders (ties to the lower layer); k_l = clip(q_l, max(1, ceil(m/100)), m), the token
+ * form of the paper's clip(beta, 0.01, 1).  No renormalisation after the clip.
+ *
+ * nnz      [B,L,Hq] uint64  in
+ * alpha    as a rational alpha_num / alpha_den, 0 < alpha <= 1
+ * k_out    [B,L] int32      out
+ * beta_out [B,L] float      out, k_l / m, may be NULL
+ */
+vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz,
+                        int64_t alpha_num, int64_t alpha_den,
+                        int32_t* k_out, float* beta_out, vlc_stream stream);
+
+/*
+ * The compressed cache.  The caller owns one device arena; the library lays out inside it
+ * the ragged per-layer K/V slabs (layer l of request b holds k[b][l] + T_max slots per KV
+ * head), the kept indices, per-layer offsets, and the split-KV scratch of decode.
+ *
+ * T_max      decode appends reserved per layer
+ * sum_k_max  upper bound on sum_l k[b][l] of one request (e.g. B_tot + L * ceil(m/100))
+ */
+typedef struct vlc_cache vlc_cache;
+
+size_t     vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max);
+vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
+                            void* arena, size_t arena_bytes, vlc_cache** out);
+void       vlc_cache_destroy(vlc_cache* cache);      /* frees host bookkeeping only */
+
+/* Where things live inside the arena (byte offsets from its base), for tests and tools.
+ * Slab of (b,l): cap = k[b][l] + T_max slots; K rows of KV head h start at
+ *   kv_off + ((slot_off[b][l] * 2 * Hkv) + h * cap) * d * elem_size,
+ * V rows at the same plus Hkv * cap * d * elem_size; kept indices of head h at
+ *   idx_off + (slot_off[b][l] * Hkv + h * cap) * 4.   Appended slots hold index m + t. */
+typedef struct {
+    size_t status_off;     /* int32[4]: sticky vlc_status, request, layer, detail */
+    size_t slot_off_off;   /* int64[B*L]: first slot of (b,l), in slots            */
+    size_t kept_off;       /* int32[B*L]: validated k[b][l]                        */
+    size_t kv_off;
+    size_t idx_off;
+    size_t scratch_off;
+    size_t total_bytes;
+    int64_t slots_per_request;
+} vlc_cache_layout;
+vlc_status vlc_cache_get_layout(const vlc_cache* cache, vlc_cache_layout* out);
+
+/* Synchronises the stream and returns the cache's sticky device-side status. */
+vlc_status vlc_cache_status(vlc_cache* cache, vlc_stream stream);
+
+/*
+ * vlc_topk_compact -- token eviction (paper Sec. 2.2 top-k set; Sec. 4.2; App. A.4 copy of the
+ * survivors into contiguous memory).  For every (b,l,hkv): keep the k[b][l] positions with the
+ * largest score (ties to the lower position), in ascending position, and gather their K and
+ * V rows into the cache.  With n_recent = r > 0 the last min(r, k) positions are kept
+ * unconditionally and TopK fills the rest.  Resets the cache's decode step count to 0.
+ *
+ * scores  [B,L,Hkv,m] float  in
+ * k       [B,L] int32        in (device; e.g. vlc_allocate's output), each in [1, m]
+ * k_full, v_full [B,L,Hkv,m,d] in, storage dtype
+ * idx_out [B,L,Hkv,m] int32  out, may be NULL: first k[b][l] entries of a row are the kept
+ *                             positions, the rest are left untouched
+ */
+vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t* k,
+                            int32_t n_recent, const void* k_full, const void* v_full,
+                            int32_t* idx_out, vlc_stream stream);
+
+/*
+ * vlc_decode_attn -- one decode step of GQA attention over the compressed cache (paper
+ * Sec. 2.1 decoding phase), for layers [layer_begin, layer_end).  If k_new != NULL the new
+ * key/value of every (b, hkv) is appended first and attended; nothing is evicted.
+ *
+ *   out[l,b,h,:] = sum_r softmax_r(sm_scale[l] * <q[l,b,h,:], Kc[b,l,h/g,r,:]>) Vc[b,l,h/g,r,:]
+ *
+ * q            [layers in range, B, Hq, d]   in, storage dtype
+ * k_new, v_new [layers in range, B, Hkv, d]  in, or both NULL (no append)
+ * sm_scale     [L] float (indexed by absolute layer) or NULL for 1/sqrt(d)
+ * out          [layers in range, B, Hq, d]   out, storage dtype
+ * All layers of one call must have received the same number of appends so far
+ * (VLC_ERR_INVALID_ARG otherwise); appending beyond T_max is VLC_ERR_CAPACITY.
+ */
+vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_end,
+                           const void* q, const void* k_new, const void* v_new,
+                           const float* sm_scale, void* out, vlc_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLCACHE_H */

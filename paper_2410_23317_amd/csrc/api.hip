@@ -1,0 +1,274 @@
+// C-ABI entry points of libvlcache: argument validation, cache bookkeeping, kernel sequencing.
+// Every entry point validates on the host first and only then enqueues kernels, so a bad call
+// never reaches the device.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+vlc_status fail(vlc_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+vlc_status hip_fail(hipError_t e, const char* where) {
+    return fail(VLC_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t elem_size(int dtype) { return dtype == VLC_F32 ? 4 : 2; }
+
+vlc_status check_shape(const vlc_shape* s) {
+    if (!s) return fail(VLC_ERR_INVALID_ARG, "shape is NULL");
+    if (s->dtype != VLC_F32 && s->dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "dtype %d is neither VLC_F32 nor VLC_BF16", s->dtype);
+    if (s->B < 1 || s->L < 1 || s->Hq < 1 || s->Hkv < 1 || s->m < 1 || s->tau < 1)
+        return fail(VLC_ERR_SHAPE, "B, L, Hq, Hkv, m, tau must be positive");
+    if (s->d != 64 && s->d != 128) return fail(VLC_ERR_SHAPE, "d = %d: only 64 and 128 are built", s->d);
+    if (s->Hq % s->Hkv != 0) return fail(VLC_ERR_SHAPE, "Hq = %d is not a multiple of Hkv = %d", s->Hq, s->Hkv);
+    const int g = s->Hq / s->Hkv;
+    if (g > 8) return fail(VLC_ERR_SHAPE, "g = Hq/Hkv = %d: at most 8 query heads per KV head", g);
+    if (s->tau > s->m) return fail(VLC_ERR_SHAPE, "tau = %d exceeds m = %d", s->tau, s->m);
+    if ((int64_t)g * s->tau > 512) return fail(VLC_ERR_SHAPE, "g * tau = %d exceeds 512 window rows per KV head", g * s->tau);
+    if (s->L > vlc::kMaxLayers) return fail(VLC_ERR_SHAPE, "L = %d exceeds %d", s->L, vlc::kMaxLayers);
+    if ((int64_t)s->B * s->L * s->Hq > 65535) return fail(VLC_ERR_SHAPE, "B * L * Hq = %lld exceeds 65535", (long long)s->B * s->L * s->Hq);
+    if ((double)s->m * s->d * s->Hkv * s->L * s->B > 4.0e12) return fail(VLC_ERR_SHAPE, "K tensor larger than 4e12 elements");
+    return VLC_OK;
+}
+
+double region_size(const vlc_shape& s) {
+    return (double)s.tau * (s.m - s.tau) + (double)s.tau * (s.tau + 1) / 2.0;
+}
+
+vlc::ScoreArgs score_args(const vlc_shape* s, const void* q_win, const void* k, const float* sm_scale, float p,
+                          float* scores, float* row_max, float* row_sum, uint64_t* nnz, void* ws, vlc_stream st) {
+    vlc::ScoreArgs a;
+    a.s = *s; a.q_win = q_win; a.k = k; a.sm_scale = sm_scale; a.p = p; a.scores = scores;
+    a.row_max = row_max; a.row_sum = row_sum; a.nnz = nnz; a.workspace = ws; a.stream = (hipStream_t)st;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* vlc_last_error_string(void) { return g_err; }
+const char* vlc_version(void) { return "vlcache-mi355x 0.1 (gfx950)"; }
+
+size_t vlc_workspace_bytes(const vlc_shape* shape) {
+    if (check_shape(shape) != VLC_OK) return 0;
+    // partial row statistics + a private copy of the row statistics for the standalone sparsity sweep
+    const size_t stats = (size_t)shape->B * shape->L * shape->Hq * shape->tau * sizeof(float);
+    return align_up(vlc::score_simple_workspace_bytes(*shape), 256) + 2 * align_up(stats, 256);
+}
+
+vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k, const float* sm_scale, float p,
+                     float* scores, float* row_max, float* row_sum, uint64_t* nnz, void* workspace,
+                     size_t workspace_bytes, vlc_stream stream) {
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!q_win || !k || !scores || !row_max || !row_sum || !workspace)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_score: q_win, k, scores, row_max, row_sum and workspace must not be NULL");
+    if (nnz && !(p > 0.f && p < 1.f)) return fail(VLC_ERR_INVALID_ARG, "vlc_score: p = %g is outside (0, 1)", p);
+    if (workspace_bytes < vlc_workspace_bytes(shape))
+        return fail(VLC_ERR_CAPACITY, "vlc_score: workspace of %zu bytes, %zu needed", workspace_bytes, vlc_workspace_bytes(shape));
+    vlc::ScoreArgs a = score_args(shape, q_win, k, sm_scale, p, scores, row_max, row_sum, nnz, workspace, stream);
+    hipError_t e = vlc::launch_rowstats_simple(a);
+    if (e != hipSuccess) return hip_fail(e, "vlc_score row statistics");
+    if (nnz) {
+        e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, a.stream);
+        if (e != hipSuccess) return hip_fail(e, "vlc_score clear counts");
+    }
+    e = vlc::launch_colsweep_simple(a);
+    if (e != hipSuccess) return hip_fail(e, "vlc_score column sweep");
+    return VLC_OK;
+}
+
+vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k, const float* sm_scale,
+                        const float* row_max, float p, uint64_t* nnz, float* gamma, void* workspace,
+                        size_t workspace_bytes, vlc_stream stream) {
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!nnz) return fail(VLC_ERR_INVALID_ARG, "vlc_sparsity: nnz must not be NULL");
+    hipStream_t hs = (hipStream_t)stream;
+    if (q_win) {
+        if (!k || !workspace) return fail(VLC_ERR_INVALID_ARG, "vlc_sparsity: k and workspace are needed for a sweep");
+        if (!(p > 0.f && p < 1.f)) return fail(VLC_ERR_INVALID_ARG, "vlc_sparsity: p = %g is outside (0, 1)", p);
+        if (workspace_bytes < vlc_workspace_bytes(shape))
+            return fail(VLC_ERR_CAPACITY, "vlc_sparsity: workspace of %zu bytes, %zu needed", workspace_bytes, vlc_workspace_bytes(shape));
+        vlc::ScoreArgs a = score_args(shape, q_win, k, sm_scale, p, nullptr, nullptr, nullptr, nnz, workspace, stream);
+        if (row_max) {
+            a.row_max = const_cast<float*>(row_max);
+        } else {
+            const size_t stats = align_up((size_t)shape->B * shape->L * shape->Hq * shape->tau * sizeof(float), 256);
+            char* tail = (char*)workspace + align_up(vlc::score_simple_workspace_bytes(*shape), 256);
+            a.row_max = (float*)tail;
+            a.row_sum = (float*)(tail + stats);
+            hipError_t e = vlc::launch_rowstats_simple(a);
+            if (e != hipSuccess) return hip_fail(e, "vlc_sparsity row statistics");
+            a.row_sum = nullptr;
+        }
+        hipError_t e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, hs);
+        if (e != hipSuccess) return hip_fail(e, "vlc_sparsity clear counts");
+        e = vlc::launch_colsweep_simple(a);
+        if (e != hipSuccess) return hip_fail(e, "vlc_sparsity count sweep");
+    }
+    if (gamma) {
+        hipError_t e = vlc::launch_gamma(*shape, nnz, gamma, hs);
+        if (e != hipSuccess) return hip_fail(e, "vlc_sparsity gamma");
+    }
+    return VLC_OK;
+}
+
+vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alpha_num, int64_t alpha_den,
+                        int32_t* k_out, float* beta_out, vlc_stream stream) {
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!nnz || !k_out) return fail(VLC_ERR_INVALID_ARG, "vlc_allocate: nnz and k_out must not be NULL");
+    if (alpha_num < 1 || alpha_den < 1 || alpha_num > alpha_den)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_allocate: alpha = %lld/%lld is outside (0, 1]", (long long)alpha_num, (long long)alpha_den);
+    const double lm = (double)shape->L * shape->m;
+    if ((double)alpha_num * lm > 9.0e18) return fail(VLC_ERR_INVALID_ARG, "vlc_allocate: alpha_num * L * m overflows");
+    const int64_t B_tot = (alpha_num * (int64_t)shape->L * shape->m) / alpha_den;
+    // n_l * B_tot must fit 64 bits: n_l <= Hq * region size
+    if ((double)shape->Hq * region_size(*shape) * (double)B_tot > 1.8e19)
+        return fail(VLC_ERR_SHAPE, "vlc_allocate: Hq * region * budget exceeds 64-bit arithmetic");
+    hipError_t e = vlc::launch_allocate(*shape, nnz, B_tot, k_out, beta_out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "vlc_allocate");
+    return VLC_OK;
+}
+
+static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, vlc_cache_layout* lay) {
+    if (vlc_status st = check_shape(s)) return st;
+    if (T_max < 0 || T_max > (1 << 24)) return fail(VLC_ERR_INVALID_ARG, "T_max = %d is out of range", T_max);
+    if (sum_k_max < s->L || sum_k_max > (int64_t)s->L * s->m)
+        return fail(VLC_ERR_INVALID_ARG, "sum_k_max = %lld is outside [L, L*m]", (long long)sum_k_max);
+    const size_t es = elem_size(s->dtype);
+    const size_t BL = (size_t)s->B * s->L;
+    const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
+    size_t off = 0;
+    lay->status_off = off;      off = align_up(off + 4 * sizeof(int32_t), 256);
+    lay->slot_off_off = off;    off = align_up(off + BL * sizeof(int64_t), 256);
+    lay->kept_off = off;        off = align_up(off + BL * sizeof(int32_t), 256);
+    lay->kv_off = off;          off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * s->d * es, 256);
+    lay->idx_off = off;         off = align_up(off + (size_t)s->B * spr * s->Hkv * sizeof(int32_t), 256);
+    lay->scratch_off = off;
+    off = align_up(off + BL * s->Hq * vlc::kMaxSplits * (s->d + 2) * sizeof(float), 256);
+    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
+    lay->total_bytes = off;
+    lay->slots_per_request = spr;
+    return VLC_OK;
+}
+
+size_t vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
+    vlc_cache_layout lay;
+    if (cache_layout(shape, T_max, sum_k_max, &lay) != VLC_OK) return 0;
+    return lay.total_bytes;
+}
+
+vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
+                            size_t arena_bytes, vlc_cache** out) {
+    if (!out) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: out is NULL");
+    *out = nullptr;
+    vlc_cache_layout lay;
+    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, &lay)) return st;
+    if (!arena) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: arena is NULL");
+    if (((uintptr_t)arena & 255) != 0) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: arena must be 256-byte aligned");
+    if (arena_bytes < lay.total_bytes)
+        return fail(VLC_ERR_CAPACITY, "vlc_cache_create: arena of %zu bytes, %zu needed", arena_bytes, lay.total_bytes);
+    vlc_cache* c = new (std::nothrow) vlc_cache;
+    if (!c) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: out of host memory");
+    memset(c, 0, sizeof(*c));
+    c->shape = *shape;
+    c->T_max = T_max;
+    c->sum_k_max = sum_k_max;
+    c->slots_per_request = lay.slots_per_request;
+    c->arena = (char*)arena;
+    c->layout = lay;
+    const size_t BL = (size_t)shape->B * shape->L;
+    c->dev.status = (int32_t*)(c->arena + lay.status_off);
+    c->dev.slot_off = (int64_t*)(c->arena + lay.slot_off_off);
+    c->dev.kept = (int32_t*)(c->arena + lay.kept_off);
+    c->dev.kv = c->arena + lay.kv_off;
+    c->dev.idx = (int32_t*)(c->arena + lay.idx_off);
+    c->dev.partials = (float*)(c->arena + lay.scratch_off);
+    c->dev.counters = (int32_t*)(c->arena + lay.scratch_off +
+                                 align_up(BL * shape->Hq * vlc::kMaxSplits * (shape->d + 2) * sizeof(float), 256));
+    c->compacted = false;
+    *out = c;
+    return VLC_OK;
+}
+
+void vlc_cache_destroy(vlc_cache* cache) { delete cache; }
+
+vlc_status vlc_cache_get_layout(const vlc_cache* cache, vlc_cache_layout* out) {
+    if (!cache || !out) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_get_layout: NULL argument");
+    *out = cache->layout;
+    return VLC_OK;
+}
+
+vlc_status vlc_cache_status(vlc_cache* cache, vlc_stream stream) {
+    if (!cache) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_status: cache is NULL");
+    if (!cache->compacted) return VLC_OK;
+    int32_t st[4] = {0, 0, 0, 0};
+    hipError_t e = hipMemcpyAsync(st, cache->dev.status, sizeof(st), hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "vlc_cache_status");
+    if (st[0] == VLC_ERR_INVALID_ARG) return fail(VLC_ERR_INVALID_ARG, "budget k[%d][%d] = %d is outside [1, m]", st[1], st[2], st[3]);
+    if (st[0] == VLC_ERR_CAPACITY) return fail(VLC_ERR_CAPACITY, "request %d: budgets plus reserved appends need %d slots, arena has %lld",
+                                               st[1], st[3], (long long)cache->slots_per_request);
+    return (vlc_status)st[0];
+}
+
+vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t* k, int32_t n_recent,
+                            const void* k_full, const void* v_full, int32_t* idx_out, vlc_stream stream) {
+    if (!cache) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: cache is NULL");
+    if (!scores || !k || !k_full || !v_full)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: scores, k, k_full and v_full must not be NULL");
+    if (n_recent < 0) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: n_recent = %d is negative", n_recent);
+    hipStream_t hs = (hipStream_t)stream;
+    hipError_t e = vlc::launch_fill_u64((uint64_t*)cache->dev.status, 2, 0, hs);     // clear the sticky flag
+    if (e != hipSuccess) return hip_fail(e, "vlc_topk_compact clear status");
+    e = vlc::launch_topk_compact(*cache, scores, k, n_recent, k_full, v_full, idx_out, hs);
+    if (e != hipSuccess) return hip_fail(e, "vlc_topk_compact");
+    cache->compacted = true;
+    memset(cache->appended, 0, sizeof(cache->appended));
+    return VLC_OK;
+}
+
+vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,
+                           const void* k_new, const void* v_new, const float* sm_scale, void* out,
+                           vlc_stream stream) {
+    if (!cache) return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn: cache is NULL");
+    if (!cache->compacted) return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn: the cache has not been filled by vlc_topk_compact");
+    if (layer_begin < 0 || layer_end > cache->shape.L || layer_begin >= layer_end)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn: layer range [%d, %d) is outside [0, %d)", layer_begin, layer_end, cache->shape.L);
+    if (!q || !out) return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn: q and out must not be NULL");
+    if ((k_new == nullptr) != (v_new == nullptr))
+        return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn: k_new and v_new must both be given or both be NULL");
+    const int appended = cache->appended[layer_begin];
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (cache->appended[l] != appended)
+            return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn: layers %d and %d have %d and %d appends; call them separately",
+                        layer_begin, l, appended, cache->appended[l]);
+    if (k_new && appended >= cache->T_max)
+        return fail(VLC_ERR_CAPACITY, "vlc_decode_attn: layer %d already holds the %d appends reserved", layer_begin, cache->T_max);
+    vlc::DecodeArgs a;
+    a.c = cache; a.layer_begin = layer_begin; a.n_layers = layer_end - layer_begin;
+    a.q = q; a.k_new = k_new; a.v_new = v_new; a.sm_scale = sm_scale; a.out = out;
+    a.appended = appended; a.stream = (hipStream_t)stream;
+    hipError_t e = vlc::launch_decode(a);
+    if (e != hipSuccess) return hip_fail(e, "vlc_decode_attn");
+    if (k_new)
+        for (int l = layer_begin; l < layer_end; ++l) cache->appended[l] += 1;
+    return VLC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Device-side helpers shared by the VL-Cache kernels (gfx950 / CDNA4, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace vlc {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kWave = 64;
+
+typedef uint16_t bf16_t;                       // raw bfloat16 bits
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (inputs here are finite).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPer16B = 4;
+    __device__ static __forceinline__ float load(const float* p) { return *p; }
+    __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int kPer16B = 8;
+    __device__ static __forceinline__ float load(const bf16_t* p) { return __uint_as_float(((uint32_t)*p) << 16); }
+    __device__ static __forceinline__ void store(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16_bits(v); }
+};
+
+// Unpack one 16-byte chunk of storage into fp32 lanes.
+__device__ __forceinline__ void unpack16(const uint4& v, float (&f)[4], const float*) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+}
+__device__ __forceinline__ void unpack16(const uint4& v, float (&f)[8], const bf16_t*) {
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- data-parallel-primitive moves: lane permutations inside a 16-lane row -------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppRowRor(int n) { return 0x120 + n; }
+constexpr int kDppQuadPerm(int a, int b, int c, int d) { return a | (b << 2) | (c << 4) | (d << 6); }
+constexpr int kDppRowHalfMirror = 0x141;
+
+// Sum over groups of LANES consecutive lanes; every lane of the group gets the total.
+template <int LANES>
+__device__ __forceinline__ float group_allreduce_sum(float x) {
+    static_assert(LANES == 4 || LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "group size");
+    if constexpr (LANES == 16) {
+        x += dpp_mov<kDppRowRor(8)>(x);
+        x += dpp_mov<kDppRowRor(4)>(x);
+        x += dpp_mov<kDppRowRor(2)>(x);
+        x += dpp_mov<kDppRowRor(1)>(x);
+    } else if constexpr (LANES == 8) {
+        x += dpp_mov<kDppRowHalfMirror>(x);
+        x += dpp_mov<kDppQuadPerm(1, 0, 3, 2)>(x);
+        x += dpp_mov<kDppQuadPerm(2, 3, 0, 1)>(x);
+    } else if constexpr (LANES == 4) {
+        x += dpp_mov<kDppQuadPerm(1, 0, 3, 2)>(x);
+        x += dpp_mov<kDppQuadPerm(2, 3, 0, 1)>(x);
+    } else {
+        for (int o = LANES / 2; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+    }
+    return x;
+}
+
+__device__ __forceinline__ float wave_allreduce_max(float x) {
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
+    return x;
+}
+__device__ __forceinline__ float wave_allreduce_sum(float x) {
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_allreduce_sum_u32(uint32_t x) {
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+
+// Device-visible sticky error: first writer wins.
+__device__ __forceinline__ void set_sticky(int32_t* status, int code, int b, int l, int detail) {
+    if (atomicCAS(status, 0, code) == 0) { status[1] = b; status[2] = l; status[3] = detail; }
+}
+
+}  // namespace vlc

@@ -1,0 +1,86 @@
+// Host-side internals of libvlcache: the cache bookkeeping and the kernel launchers that the
+// C-ABI entry points (api.hip) call after validating their arguments.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "vlcache.h"
+
+namespace vlc {
+
+constexpr int kMaxSplits = 16;         // split-KV blocks per (b, l, kv head) row of decode
+constexpr int kMaxLayers = 1024;
+constexpr int kScoreChunk = 256;       // keys per block of the generic scoring sweeps
+
+struct CacheDev {                      // device pointers into the caller's arena
+    int32_t* status;                   // [4]
+    int64_t* slot_off;                 // [B*L]
+    int32_t* kept;                     // [B*L]
+    char* kv;
+    int32_t* idx;
+    float* partials;                   // [B*L*Hq][kMaxSplits][d + 2]
+    int32_t* counters;                 // [B*L*Hkv]
+};
+
+}  // namespace vlc
+
+struct vlc_cache {
+    vlc_shape shape;
+    int32_t T_max;
+    int64_t sum_k_max;
+    int64_t slots_per_request;
+    char* arena;
+    vlc_cache_layout layout;
+    vlc::CacheDev dev;
+    bool compacted;
+    int32_t appended[vlc::kMaxLayers]; // decode appends so far, per layer
+};
+
+namespace vlc {
+
+// ---- scoring sweeps (score_simple.hip: any dtype; score_mfma.hip: bf16 matrix-core path) ----
+struct ScoreArgs {
+    vlc_shape s;
+    const void* q_win;
+    const void* k;
+    const float* sm_scale;      // may be null
+    float p;
+    float* scores;              // null: count only
+    float* row_max;
+    float* row_sum;
+    uint64_t* nnz;              // null: no counting
+    void* workspace;
+    hipStream_t stream;
+};
+size_t score_simple_workspace_bytes(const vlc_shape& s);
+hipError_t launch_rowstats_simple(const ScoreArgs& a);     // fills row_max, row_sum
+hipError_t launch_colsweep_simple(const ScoreArgs& a);     // scores and/or nnz from row_max,row_sum
+hipError_t launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t st);
+hipError_t launch_gamma(const vlc_shape& s, const uint64_t* nnz, float* gamma, hipStream_t st);
+
+// ---- allocation ----
+hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t B_tot,
+                           int32_t* k_out, float* beta_out, hipStream_t st);
+
+// ---- eviction ----
+hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const int32_t* k,
+                               int32_t n_recent, const void* k_full, const void* v_full,
+                               int32_t* idx_out, hipStream_t st);
+
+// ---- decode ----
+struct DecodeArgs {
+    const vlc_cache* c;
+    int layer_begin, n_layers;
+    const void* q;
+    const void* k_new;
+    const void* v_new;
+    const float* sm_scale;
+    void* out;
+    int appended;               // appends of these layers BEFORE this call
+    hipStream_t stream;
+};
+hipError_t launch_decode(const DecodeArgs& a);
+
+}  // namespace vlc

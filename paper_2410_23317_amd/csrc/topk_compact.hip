@@ -1,0 +1,219 @@
+// Token eviction: per-(request, layer, KV head) TopK of the accumulated post-vision scores
+// (paper Sec. 2.2 top-k set, Sec. 4.2) and the copy of the surviving K/V rows into the contiguous,
+// ragged per-layer cache (App. A.4).  Three kernels on one stream:
+//   layout : validates k[b][l], prefix-sums the slab offsets of a request's layers
+//   select : radix-select of the k-th largest score, then an ordered compaction that emits the
+//            kept positions ascending (ties to the lower position)
+//   gather : streams the kept 16-byte row chunks of K and V into the slabs
+#include "common.h"
+#include "internal.h"
+
+namespace vlc {
+namespace {
+
+__global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, int L, int Hkv, int m,
+                                                     int T_max, int64_t slots_per_request, CacheDev dev) {
+    __shared__ int32_t kept_s[kMaxLayers];
+    __shared__ int64_t pre[kMaxLayers];
+    __shared__ int bad;
+    const int b = blockIdx.x;
+    if (threadIdx.x == 0) bad = 0;
+    for (int l = threadIdx.x; l < L; l += blockDim.x) {
+        int kk = k[(size_t)b * L + l];
+        if (kk < 1 || kk > m) {
+            set_sticky(dev.status, VLC_ERR_INVALID_ARG, b, l, kk);
+            kk = 0;
+        }
+        kept_s[l] = kk;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t acc = 0;
+        for (int l = 0; l < L; ++l) { pre[l] = acc; acc += kept_s[l] + T_max; }
+        if (acc > slots_per_request) {
+            set_sticky(dev.status, VLC_ERR_CAPACITY, b, -1, (int)min(acc, (int64_t)INT32_MAX));
+            bad = 1;
+        }
+    }
+    __syncthreads();
+    for (int l = threadIdx.x; l < L; l += blockDim.x) {
+        // a request whose budgets do not fit keeps nothing: every later kernel skips its rows
+        dev.slot_off[(size_t)b * L + l] = (int64_t)b * slots_per_request + (bad ? (int64_t)l * T_max : pre[l]);
+        dev.kept[(size_t)b * L + l] = bad ? 0 : kept_s[l];
+    }
+    for (int x = threadIdx.x; x < L * Hkv; x += blockDim.x) dev.counters[(size_t)b * L * Hkv + x] = 0;
+}
+
+// Order-preserving map float -> uint32 (larger float, larger key).
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kSelThreads = 512;
+constexpr int kSelWaves = kSelThreads / 64;
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, CacheDev dev,
+                                                             int Hkv, int m, int T_max, int n_recent,
+                                                             int32_t* __restrict__ idx_out) {
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sel_bin, sel_above;
+    __shared__ uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
+    const int row = blockIdx.x;
+    const int hkv = row % Hkv, bl = row / Hkv;
+    const int kk = dev.kept[bl];
+    if (kk == 0) return;
+    const int rcnt = min(max(n_recent, 0), kk);
+    const int need = kk - rcnt;                // picked by score among positions [0, mc)
+    const int mc = m - rcnt;
+    const int cap = kk + T_max;
+    const float* s = scores + (size_t)row * m;
+    int32_t* out = dev.idx + dev.slot_off[bl] * Hkv + (int64_t)hkv * cap;
+    int32_t* out2 = idx_out ? idx_out + (size_t)row * m : nullptr;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)need;
+    if (need > 0) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            for (int j = tid; j < mc; j += kSelThreads) {
+                const uint32_t u = order_key(s[j]);
+                if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (wave == 0) {
+                // lane i owns bins 4i..4i+3; find the highest bin whose count, added to everything
+                // above it, reaches `remaining`
+                uint32_t c[4];
+#pragma unroll
+                for (int x = 0; x < 4; ++x) c[x] = hist[lane * 4 + x];
+                const uint32_t tot = c[0] + c[1] + c[2] + c[3];
+                uint32_t suf = tot;             // inclusive suffix sum over lanes >= this one
+                for (int o = 1; o < 64; o <<= 1) {
+                    const uint32_t v = __shfl_down(suf, o, 64);
+                    if (lane + o < 64) suf += v;
+                }
+                uint32_t above = suf - tot;
+                if (above < remaining && remaining <= above + tot) {
+#pragma unroll
+                    for (int x = 3; x >= 0; --x) {
+                        if (above + c[x] >= remaining) { sel_bin = lane * 4 + x; sel_above = above; break; }
+                        above += c[x];
+                    }
+                }
+            }
+            __syncthreads();
+            prefix |= sel_bin << shift;
+            mask |= 0xffu << shift;
+            remaining -= sel_above;            // those above are all kept; keep looking inside the bin
+            __syncthreads();
+        }
+    }
+    // `prefix` is now the key of the need-th largest candidate; `remaining` of the candidates equal
+    // to it are kept, lowest positions first.
+    const int seg = ((mc + kSelWaves - 1) / kSelWaves + 63) & ~63;
+    const int j0 = wave * seg, j1 = min(mc, j0 + seg);
+    uint32_t gt = 0, eq = 0;
+    if (need > 0) {
+        for (int j = j0 + lane; j < j1; j += 64) {
+            const uint32_t u = order_key(s[j]);
+            gt += (u > prefix) ? 1u : 0u;
+            eq += (u == prefix) ? 1u : 0u;
+        }
+        gt = wave_allreduce_sum_u32(gt);
+        eq = wave_allreduce_sum_u32(eq);
+    }
+    if (lane == 0) { cnt_gt[wave] = gt; cnt_eq[wave] = eq; }
+    __syncthreads();
+    if (need > 0) {
+        uint32_t gt_run = 0, eq_run = 0;
+        for (int w = 0; w < wave; ++w) { gt_run += cnt_gt[w]; eq_run += cnt_eq[w]; }
+        const unsigned long long lt_mask = (1ull << lane) - 1ull;
+        for (int jb = j0; jb < j1; jb += 64) {
+            const int j = jb + lane;
+            const bool in = j < j1;
+            const uint32_t u = in ? order_key(s[j]) : 0u;
+            const bool is_gt = in && (u > prefix);
+            const bool is_eq = in && (u == prefix);
+            const unsigned long long bg = __ballot(is_gt), be = __ballot(is_eq);
+            const uint32_t eq_rank = eq_run + (uint32_t)__popcll(be & lt_mask);
+            const bool take = is_gt || (is_eq && eq_rank < remaining);
+            const unsigned long long bs = __ballot(take);
+            if (take) {
+                const uint32_t pos = gt_run + min(eq_run, remaining) + (uint32_t)__popcll(bs & lt_mask);
+                out[pos] = j;
+                if (out2) out2[pos] = j;
+            }
+            gt_run += (uint32_t)__popcll(bg);
+            eq_run += (uint32_t)__popcll(be);
+        }
+    }
+    for (int x = tid; x < rcnt; x += kSelThreads) {     // forced recent window
+        out[need + x] = mc + x;
+        if (out2) out2[need + x] = mc + x;
+    }
+}
+
+template <int ROWBYTES>
+__global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_full, const char* __restrict__ v_full,
+                                                     CacheDev dev, int Hkv, int m, int T_max) {
+    constexpr int LPR = ROWBYTES / 16;          // lanes per row
+    constexpr int RPB = 256 / LPR;              // rows per block step
+    constexpr int U = 4;
+    const int row = blockIdx.y;
+    const int hkv = row % Hkv, bl = row / Hkv;
+    const int kk = dev.kept[bl];
+    if (kk == 0) return;
+    const int cap = kk + T_max;
+    const int64_t so = dev.slot_off[bl];
+    uint4* kd = reinterpret_cast<uint4*>(dev.kv + ((so * 2 * Hkv) + (int64_t)hkv * cap) * ROWBYTES);
+    uint4* vd = kd + (int64_t)Hkv * cap * LPR;
+    const uint4* ks = reinterpret_cast<const uint4*>(k_full + (size_t)row * m * ROWBYTES);
+    const uint4* vs = reinterpret_cast<const uint4*>(v_full + (size_t)row * m * ROWBYTES);
+    const int32_t* idx = dev.idx + so * Hkv + (int64_t)hkv * cap;
+    const int c = threadIdx.x % LPR, sub = threadIdx.x / LPR;
+    for (int r0 = blockIdx.x * RPB * U; r0 < kk; r0 += gridDim.x * RPB * U) {
+        uint4 a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + u * RPB + sub;
+            if (r < kk) {
+                const int64_t j = idx[r];
+                a[u] = ks[j * LPR + c];
+                b[u] = vs[j * LPR + c];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = r0 + u * RPB + sub;
+            if (r < kk) {
+                kd[(int64_t)r * LPR + c] = a[u];
+                vd[(int64_t)r * LPR + c] = b[u];
+            }
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const int32_t* k, int32_t n_recent,
+                               const void* k_full, const void* v_full, int32_t* idx_out, hipStream_t st) {
+    const vlc_shape& s = c.shape;
+    const int rows = s.B * s.L * s.Hkv;
+    layout_kernel<<<s.B, 256, 0, st>>>(k, s.L, s.Hkv, s.m, c.T_max, c.slots_per_request, c.dev);
+    select_kernel<<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, idx_out);
+    const int rowbytes = s.d * (s.dtype == VLC_F32 ? 4 : 2);
+    int gx = (4096 + rows - 1) / rows;
+    gx = gx < 1 ? 1 : (gx > 32 ? 32 : gx);
+    dim3 grid(gx, rows);
+    const char* kf = (const char*)k_full;
+    const char* vf = (const char*)v_full;
+    if (rowbytes == 128) gather_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.Hkv, s.m, c.T_max);
+    else if (rowbytes == 256) gather_kernel<256><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.Hkv, s.m, c.T_max);
+    else gather_kernel<512><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.Hkv, s.m, c.T_max);
+    return hipGetLastError();
+}
+
+}  // namespace vlc
