@@ -1,0 +1,199 @@
+"""Benchmark of the VL-Cache hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic request batch that is already
+resident in HBM: compression (vlc_score -> vlc_sparsity -> vlc_allocate -> vlc_topk_compact) and then
+T decode steps of vlc_decode_attn, each one ragged launch over all layers.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "KV compress ms/request; decode-attn µs/layer-step @10% budget; % HBM peak"
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="workload id (1 = 7B shape, m=2944: the headline)")
+    ap.add_argument("--alpha", type=int, default=-1, help="index into the config's budget list (default: the 10%% one)")
+    ap.add_argument("--decode-steps", type=int, default=-1)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import workloads as W
+    import paper_2410_23317_amd as V
+    from paper_2410_23317_amd.pipeline import VLCachePath
+
+    cfg = W.CONFIGS[args.config]
+    alpha = cfg.alphas[args.alpha] if args.alpha >= 0 else ((1, 10) if (1, 10) in cfg.alphas else cfg.alphas[0])
+    T = args.decode_steps if args.decode_steps > 0 else cfg.steps
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    dt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    es = 4 if cfg.dtype == "f32" else 2
+
+    # ---- synthetic inputs, resident in HBM before anything is timed
+    t0 = time.time()
+    q_win = torch.empty((cfg.B, cfg.L, cfg.Hq, cfg.tau, cfg.d), dtype=dt, device=dev)
+    k = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.m, cfg.d), dtype=dt, device=dev)
+    v = torch.empty_like(k)
+
+    def put(b, l, t):
+        q_win[b, l].copy_(torch.from_numpy(t["q_win"]).to(dt))
+        k[b, l].copy_(torch.from_numpy(t["k"]).to(dt))
+        v[b, l].copy_(torch.from_numpy(t["v"]).to(dt))
+
+    W.for_each_layer(cfg, put, workers=min(16, os.cpu_count() or 8))
+    sm = torch.from_numpy(W.sm_scale(cfg)).to(dev)
+    dq = torch.empty((T, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device=dev)
+    dk = torch.empty((T, cfg.L, cfg.B, cfg.Hkv, cfg.d), dtype=dt, device=dev)
+    dv = torch.empty_like(dk)
+    for t in range(T):
+        d = W.decode_step_inputs(cfg, t)
+        dq[t].copy_(torch.from_numpy(d["q"]).to(dt))
+        dk[t].copy_(torch.from_numpy(d["k_new"]).to(dt))
+        dv[t].copy_(torch.from_numpy(d["v_new"]).to(dt))
+    out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device=dev)
+    gen_s = time.time() - t0
+
+    shape = V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
+    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=T)
+
+    def one_step(ev=None):
+        if ev: ev[0].record()
+        path.compress(q_win, k, v, sm)
+        if ev: ev[1].record()
+        for t in range(T):
+            path.decode(0, cfg.L, dq[t], dk[t], dv[t], sm, out)
+        if ev: ev[2].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    path.status()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    path.status()
+    comp_ms = float(np.median([e[0].elapsed_time(e[1]) for e in events]))
+    dec_ms = [e[1].elapsed_time(e[2]) for e in events]
+    dec_launch_us = float(np.mean(dec_ms)) * 1e3 / T                    # mean duration of one ragged all-layer launch
+    dec_us_layer_step = dec_launch_us / cfg.L
+
+    # ---- the same decode work issued as one launch per layer (how a model would call it)
+    path.compress(q_win, k, v, sm)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(T):
+        for l in range(cfg.L):
+            path.decode(l, l + 1, dq[t, l], dk[t, l], dv[t, l], sm, out[l])
+    e1.record()
+    torch.cuda.synchronize()
+    per_layer_us = e0.elapsed_time(e1) * 1e3 / (T * cfg.L)
+
+    # ---- algorithmic bytes of one decode launch (Kc + Vc rows read once, q / out / appended rows)
+    kk = path.k.cpu().numpy().astype(np.int64)                            # [B, L]
+    mean_len = kk.sum() + cfg.B * cfg.L * (T + 1) / 2.0                   # sum over (b,l) of the mean slot count
+    kv_bytes = 2.0 * cfg.Hkv * cfg.d * es * mean_len
+    io_bytes = cfg.B * cfg.L * (2 * cfg.Hq + 2 * cfg.Hkv) * cfg.d * es
+    alg_bytes = kv_bytes + io_bytes
+    achieved = alg_bytes / (dec_launch_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "decode_kernel (one ragged launch over all layers)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": int(alg_bytes), "launch_us": round(dec_launch_us, 3)}
+
+    result = {
+        "metric": METRIC, "value": round(comp_ms / cfg.B, 4), "unit": "ms/request (KV compress)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"cfg{cfg.cid} {cfg.name}: B={cfg.B} L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} d={cfg.d} "
+                               f"m={cfg.m} {cfg.layout()} tau={cfg.tau} alpha={alpha[0]}/{alpha[1]} p=0.01 "
+                               f"decode_steps={T}"},
+        "components": {"compress_ms_per_batch": round(comp_ms, 4), "compress_ms_per_request": round(comp_ms / cfg.B, 4),
+                       "decode_attn_us_per_layer_step": round(dec_us_layer_step, 4),
+                       "decode_attn_us_per_layer_step_one_launch_per_layer": round(per_layer_us, 4),
+                       "decode_pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+                       "budgets_request0": kk[0].tolist(), "input_generation_s": round(gen_s, 1)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(cfg, alpha, args.cpu_seconds)
+    print(json.dumps(result))
+    return 0
+
+
+def cpu_baseline(cfg, alpha, budget_s):
+    """The CPU oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    import numpy as np
+
+    import workloads as W
+    from oracle import vlcache_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    scales = W.sm_scale(cfg)
+    t_score, layers, psis, nnzs = 0.0, [], [], []
+    for l in range(cfg.L):
+        t = W.layer_inputs(cfg, 0, l)
+        c0 = time.perf_counter()
+        psi, _, _, _ = O.score(t["q_win"], t["k"], scales[l])
+        nnz, _ = O.sparsity(t["q_win"], t["k"], scales[l], 0.01)
+        t_score += time.perf_counter() - c0
+        layers.append(t); psis.append(psi); nnzs.append(nnz)
+        if t_score > budget_s * 0.6:
+            break
+    n = len(layers)
+    c0 = time.perf_counter()
+    # budgets need every layer's counts; the sample reuses the sampled layers' counts cyclically
+    nnz_all = np.stack([nnzs[l % n] for l in range(cfg.L)])
+    kk, _ = O.allocate(nnz_all, cfg.m, alpha[0], alpha[1])
+    cache = O.CompressedCache(1, n, cfg.Hkv)
+    for l in range(n):
+        cache.fill_layer(0, l, psis[l], int(kk[l]), layers[l]["k"], layers[l]["v"])
+    t_evict = time.perf_counter() - c0
+    steps, t_dec = 0, 0.0
+    while steps < cfg.steps and t_dec < budget_s * 0.3:
+        draws = [W.decode_inputs(cfg, steps, l) for l in range(n)]
+        c0 = time.perf_counter()
+        for l, d in enumerate(draws):
+            cache.decode_layer(l, d["q"][:1], d["k_new"][:1], d["v_new"][:1], scales[l])
+        t_dec += time.perf_counter() - c0
+        steps += 1
+    comp_ms = (t_score + t_evict) / n * cfg.L * 1e3
+    return {"value": round(comp_ms, 2), "unit": "ms/request (KV compress)", "cores": int(cores), "kind": "oracle",
+            "decode_attn_us_per_layer_step": round(t_dec / max(1, steps * n) * 1e6, 1),
+            "sample": f"request 0: score+sparsity+topk+gather on {n} of {cfg.L} layers scaled to {cfg.L}; "
+                      f"decode {steps} steps x {n} layers, one request"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

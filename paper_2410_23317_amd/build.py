@@ -15,7 +15,7 @@ LIB = os.path.join(HERE, "libvlcache.so")
 SOURCES = ["api.hip", "score_simple.hip", "allocate.hip", "topk_compact.hip", "decode.hip"]
 
 # packed fp32 VALU ops are switched off for all device code
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("VLC_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -3,6 +3,7 @@
 // never reaches the device.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -145,14 +146,31 @@ vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alp
     return VLC_OK;
 }
 
-static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, vlc_cache_layout* lay) {
+struct ArenaPlan {
+    vlc_cache_layout lay;
+    size_t items_off, layer_start_off, row_first_off, partials_off, counters_off;
+    int32_t unit_slots;
+    int64_t max_items;
+};
+
+static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, ArenaPlan* plan) {
     if (vlc_status st = check_shape(s)) return st;
     if (T_max < 0 || T_max > (1 << 24)) return fail(VLC_ERR_INVALID_ARG, "T_max = %d is out of range", T_max);
     if (sum_k_max < s->L || sum_k_max > (int64_t)s->L * s->m)
         return fail(VLC_ERR_INVALID_ARG, "sum_k_max = %lld is outside [L, L*m]", (long long)sum_k_max);
+    vlc_cache_layout* lay = &plan->lay;
     const size_t es = elem_size(s->dtype);
     const size_t BL = (size_t)s->B * s->L;
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
+    // decode block-unit: 512 slots unless the mean row is short (measured: per-unit overhead, not
+    // balance, dominates on MI355X once a launch has a few hundred units)
+    plan->unit_slots = (sum_k_max / s->L + T_max / 2 >= 192) ? 512 : 256;
+    if (const char* e = getenv("VLC_UNIT_SLOTS")) {           // tuning knob
+        const int v = atoi(e);
+        if (v == 128 || v == 256 || v == 512) plan->unit_slots = v;
+    }
+    plan->max_items = (int64_t)s->Hkv * ((int64_t)s->B * spr / plan->unit_slots + (int64_t)BL);
+    const int g = s->Hq / s->Hkv;
     size_t off = 0;
     lay->status_off = off;      off = align_up(off + 4 * sizeof(int32_t), 256);
     lay->slot_off_off = off;    off = align_up(off + BL * sizeof(int64_t), 256);
@@ -160,25 +178,29 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     lay->kv_off = off;          off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * s->d * es, 256);
     lay->idx_off = off;         off = align_up(off + (size_t)s->B * spr * s->Hkv * sizeof(int32_t), 256);
     lay->scratch_off = off;
-    off = align_up(off + BL * s->Hq * vlc::kMaxSplits * (s->d + 2) * sizeof(float), 256);
-    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
+    plan->items_off = off;        off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
+    plan->layer_start_off = off;  off = align_up(off + (size_t)(s->L + 1) * sizeof(int32_t), 256);
+    plan->row_first_off = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
+    plan->partials_off = off;     off = align_up(off + (size_t)plan->max_items * g * (s->d + 2) * sizeof(float), 256);
+    plan->counters_off = off;     off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
     lay->total_bytes = off;
     lay->slots_per_request = spr;
     return VLC_OK;
 }
 
 size_t vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
-    vlc_cache_layout lay;
-    if (cache_layout(shape, T_max, sum_k_max, &lay) != VLC_OK) return 0;
-    return lay.total_bytes;
+    ArenaPlan plan;
+    if (cache_layout(shape, T_max, sum_k_max, &plan) != VLC_OK) return 0;
+    return plan.lay.total_bytes;
 }
 
 vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
                             size_t arena_bytes, vlc_cache** out) {
     if (!out) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: out is NULL");
     *out = nullptr;
-    vlc_cache_layout lay;
-    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, &lay)) return st;
+    ArenaPlan plan;
+    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, &plan)) return st;
+    const vlc_cache_layout& lay = plan.lay;
     if (!arena) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: arena is NULL");
     if (((uintptr_t)arena & 255) != 0) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: arena must be 256-byte aligned");
     if (arena_bytes < lay.total_bytes)
@@ -192,15 +214,18 @@ vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k
     c->slots_per_request = lay.slots_per_request;
     c->arena = (char*)arena;
     c->layout = lay;
-    const size_t BL = (size_t)shape->B * shape->L;
+    c->unit_slots = plan.unit_slots;
+    c->max_items = plan.max_items;
     c->dev.status = (int32_t*)(c->arena + lay.status_off);
     c->dev.slot_off = (int64_t*)(c->arena + lay.slot_off_off);
     c->dev.kept = (int32_t*)(c->arena + lay.kept_off);
     c->dev.kv = c->arena + lay.kv_off;
     c->dev.idx = (int32_t*)(c->arena + lay.idx_off);
-    c->dev.partials = (float*)(c->arena + lay.scratch_off);
-    c->dev.counters = (int32_t*)(c->arena + lay.scratch_off +
-                                 align_up(BL * shape->Hq * vlc::kMaxSplits * (shape->d + 2) * sizeof(float), 256));
+    c->dev.items = (vlc::WorkItem*)(c->arena + plan.items_off);
+    c->dev.layer_item_start = (int32_t*)(c->arena + plan.layer_start_off);
+    c->dev.row_item_first = (int32_t*)(c->arena + plan.row_first_off);
+    c->dev.partials = (float*)(c->arena + plan.partials_off);
+    c->dev.counters = (int32_t*)(c->arena + plan.counters_off);
     c->compacted = false;
     *out = c;
     return VLC_OK;

@@ -1,17 +1,30 @@
 // GQA decode attention over the compressed, ragged per-layer cache (paper Sec. 2.1, decoding
 // phase: the new key/value is appended, then softmax(q K^T / sqrt d) V over every cached slot).
 //
-// Bandwidth-bound: every K and V row is read once, coalesced (16 bytes per lane, LPR lanes per
-// row), and serves all g query heads of its KV group from registers.  Work unit = one wave and
-// one tile of 64 slots:
-//   1. logits: packed-bf16 dot products (v_dot2_f32_bf16) against the g query rows held in
-//      registers, reduced over the LPR lanes of a row with DPP rotations, parked in LDS;
-//   2. softmax over the tile with lane = slot (wave-wide max / sum), running max and sum per head;
-//   3. P.V with the V rows streamed the same way, probabilities broadcast from LDS.
-// Tiles of a row are dealt round-robin to the 4*S waves of its S blocks (split-KV); the block merges
-// its waves through LDS and, if S > 1, the last block to finish (device-scope counter) merges the
-// S partial results.  Matrix cores are not used: with g <= 8 query rows per KV head the work is a
-// stream, not a contraction.
+// Bandwidth-bound: every K and V row is read once and serves all g query heads of its KV group.
+// Rows are ragged (layer budgets differ by 25x), so the work is cut into block-units of BK slots
+// listed in a device-side work list that vlc_topk_compact builds; a call launches one block per
+// unit of the slice of the list that belongs to its layer range.  Inside a block-unit each of
+// the 4 waves owns NT tiles of 32 slots:
+//   1. K and V rows are loaded 16 bytes per lane (LPR lanes per row, fully coalesced), all
+//      issued before any arithmetic;
+//   2. logits: packed-bf16 dot products (v_dot2_f32_bf16) against the g query rows held in
+//      registers, summed over the LPR lanes of a row with DPP rotations, parked in LDS;
+//   3. softmax bookkeeping with one 16-lane row per head (DPP row reductions only), the
+//      probabilities parked in LDS as bf16 pairs;
+//   4. P.V with the K lane mapping: two slots at a time through v_perm + v_dot2_f32_bf16 with
+//      the probability pairs broadcast from LDS (fp32 FMAs for fp32 storage); the 64/LPR row
+//      groups of a wave are summed once per block-unit.
+// The 4 waves merge through LDS.  A row that spans several block-units leaves unnormalised
+// partials in scratch; the unit that finishes last (device-scope counter) merges them.  The
+// partials and the counter are only ever touched with device-scope atomic accesses, which
+// are coherent across the XCDs' L2 caches by themselves, so no cache-wide release/acquire
+// fence is needed (those cost tens of microseconds here).  Matrix cores are not used: with
+// g <= 8 query rows per KV head the work is a stream, not a contraction.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "common.h"
 #include "internal.h"
 
@@ -26,8 +39,9 @@ struct DecodeParams {
     const float* sm_scale;
     CacheDev dev;
     int B, L, Hq, Hkv, m;
-    int layer_begin, T_max, S;
+    int layer_begin, n_layers, T_max;
     int appended;            // appends before this call
+    int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
     float default_scale;
 };
 
@@ -49,227 +63,427 @@ template <> __device__ __forceinline__ float dot16<float>(const uint4& a, const 
 
 constexpr int pad_pow2(int g) { return g <= 1 ? 1 : (g <= 2 ? 2 : (g <= 4 ? 4 : 8)); }
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void decode_kernel(DecodeParams P) {
-    constexpr int EP = Elem<T>::kPer16B;        // elements in a 16-byte chunk
-    constexpr int LPR = D / EP;                 // lanes per K/V row
-    constexpr int KPI = 64 / LPR;               // rows per wave load
-    constexpr int TK = 64;                      // slots per tile
-    constexpr int NIT = TK / KPI;
-    constexpr int UB = NIT < 8 ? NIT : 8;       // loads in flight per batch
-    constexpr int GP = pad_pow2(G);
+__device__ __forceinline__ void store_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Merge the nu partials (unnormalised output, running max, running sum) of one row; partials
+// of consecutive units of a row are consecutive.  COHERENT: read with device-scope loads.
+template <typename T, int D, int G, bool COHERENT>
+__device__ __forceinline__ void merge_partials(const float* part, T* outp, int nu, int tid) {
     constexpr int DP = D + 2;
-    static_assert(G <= LPR, "one lane per head needed when parking logits");
-
-    __shared__ __align__(16) float sP[4][TK][GP];
-    __shared__ float sMerge[4][G][DP];
-    __shared__ int sLast;
-
-    const int S = P.S;
-    const int row = blockIdx.x / S, split = blockIdx.x % S;
-    const int hkv = row % P.Hkv;
-    const int b = (row / P.Hkv) % P.B;
-    const int lr = row / (P.Hkv * P.B);
-    const int l = P.layer_begin + lr;
-    const int bl = b * P.L + l;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int sub = lane / LPR, c = lane % LPR;
-
-    T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + b) * P.Hq + (size_t)hkv * G) * D;
-    const int kept = P.dev.kept[bl];
-    if (kept == 0) {                            // request rejected at compaction: defined output, no reads
-        if (split == 0)
-            for (int x = tid; x < G * D; x += 256) Elem<T>::store(outp + x, 0.f);
-        return;
-    }
-    const bool appending = P.k_new != nullptr;
-    const int len = kept + P.appended + (appending ? 1 : 0);
-    const int cap = kept + P.T_max;
-    const int new_slot = appending ? len - 1 : -1;
-    const T* Kbase = reinterpret_cast<const T*>(P.dev.kv) + ((P.dev.slot_off[bl] * 2 * P.Hkv) + (int64_t)hkv * cap) * D;
-    const T* Vbase = Kbase + (int64_t)P.Hkv * cap * D;
-    const T* knew = reinterpret_cast<const T*>(P.k_new) + ((size_t)(lr * P.B + b) * P.Hkv + hkv) * D;
-    const T* vnew = reinterpret_cast<const T*>(P.v_new) + ((size_t)(lr * P.B + b) * P.Hkv + hkv) * D;
-    const float scale2 = (P.sm_scale ? P.sm_scale[l] : P.default_scale) * kLog2e;
-
-    uint4 qv[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-        qv[h] = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.q) +
-                                                ((size_t)(lr * P.B + b) * P.Hq + (size_t)hkv * G + h) * D + c * EP);
-
-    float m_run[G], l_run[G], acc[G][EP];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-        m_run[h] = -INFINITY;
-        l_run[h] = 0.f;
-#pragma unroll
-        for (int e = 0; e < EP; ++e) acc[h][e] = 0.f;
-    }
-
-    const int nW = 4 * S, wid = split * 4 + wave;
-    const int ntiles = (len + TK - 1) / TK;
-    for (int tile = wid; tile < ntiles; tile += nW) {
-        const int t0 = tile * TK;
-        // ---- 1. logits of 64 slots -> LDS
-#pragma unroll
-        for (int ib = 0; ib < NIT; ib += UB) {
-            uint4 kb[UB];
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                const int key = t0 + (ib + u) * KPI + sub;
-                const T* src = (key == new_slot) ? knew : Kbase + (int64_t)key * D;
-                kb[u] = (key < len) ? *reinterpret_cast<const uint4*>(src + c * EP) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                const int key = t0 + (ib + u) * KPI + sub;
-                float mine = 0.f;
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    const float tot = group_allreduce_sum<LPR>(dot16<T>(kb[u], qv[h], 0.f));
-                    mine = (c == h) ? tot : mine;
-                }
-                if (c < G) sP[wave][(ib + u) * KPI + sub][c] = (key < len) ? mine * scale2 : -INFINITY;
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-        // ---- 2. softmax bookkeeping, lane = slot
-        float corr[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-            const float x = sP[wave][lane][h];
-            const float m_new = fmaxf(m_run[h], wave_allreduce_max(x));     // finite: the tile has >= 1 slot
-            const float pr = exp2_fast(x - m_new);
-            corr[h] = exp2_fast(m_run[h] - m_new);
-            l_run[h] = l_run[h] * corr[h] + wave_allreduce_sum(pr);
-            m_run[h] = m_new;
-            sP[wave][lane][h] = pr;
-        }
-#pragma unroll
-        for (int h = 0; h < G; ++h)
-#pragma unroll
-            for (int e = 0; e < EP; ++e) acc[h][e] *= corr[h];
-        __builtin_amdgcn_wave_barrier();
-        // ---- 3. P.V
-#pragma unroll
-        for (int ib = 0; ib < NIT; ib += UB) {
-            uint4 vb[UB];
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                const int key = t0 + (ib + u) * KPI + sub;
-                const T* src = (key == new_slot) ? vnew : Vbase + (int64_t)key * D;
-                vb[u] = (key < len) ? *reinterpret_cast<const uint4*>(src + c * EP) : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                float f[EP];
-                unpack16(vb[u], f, (const T*)nullptr);
-                const float* pp = &sP[wave][(ib + u) * KPI + sub][0];
-#pragma unroll
-                for (int h = 0; h < G; ++h) {
-                    const float ph = pp[h];
-#pragma unroll
-                    for (int e = 0; e < EP; ++e) acc[h][e] = fmaf(ph, f[e], acc[h][e]);
-                }
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-    }
-
-    // The wave that owns the tile of the new slot also stores the new row into the cache.
-    if (appending && ((new_slot / TK) % nW) == wid && sub == 0) {
-        T* kdst = const_cast<T*>(Kbase) + (int64_t)new_slot * D;
-        T* vdst = const_cast<T*>(Vbase) + (int64_t)new_slot * D;
-        *reinterpret_cast<uint4*>(kdst + c * EP) = *reinterpret_cast<const uint4*>(knew + c * EP);
-        *reinterpret_cast<uint4*>(vdst + c * EP) = *reinterpret_cast<const uint4*>(vnew + c * EP);
-        if (c == 0) P.dev.idx[P.dev.slot_off[bl] * P.Hkv + (int64_t)hkv * cap + new_slot] = P.m + P.appended;
-    }
-
-    // ---- merge the KPI row groups of the wave, then the 4 waves of the block
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1)
-#pragma unroll
-        for (int h = 0; h < G; ++h)
-#pragma unroll
-            for (int e = 0; e < EP; ++e) acc[h][e] += __shfl_xor(acc[h][e], off, 64);
-    if (sub == 0) {
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-#pragma unroll
-            for (int e = 0; e < EP; ++e) sMerge[wave][h][c * EP + e] = acc[h][e];
-            if (c == 0) { sMerge[wave][h][D] = m_run[h]; sMerge[wave][h][D + 1] = l_run[h]; }
-        }
-    }
-    __syncthreads();
-    float* part = P.dev.partials + ((size_t)bl * P.Hq + (size_t)hkv * G) * kMaxSplits * DP;
+    constexpr int UNIT = G * DP;
     for (int x = tid; x < G * D; x += 256) {
         const int h = x / D, e = x % D;
-        float mt = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) mt = fmaxf(mt, sMerge[w][h][D]);
-        float o = 0.f, lt = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float mw = sMerge[w][h][D];
-            const float wgt = (mw > -INFINITY) ? exp2_fast(mw - mt) : 0.f;
-            o = fmaf(sMerge[w][h][e], wgt, o);
-            lt = fmaf(sMerge[w][h][D + 1], wgt, lt);
-        }
-        if (S == 1) {
-            Elem<T>::store(outp + x, o / lt);
-        } else {
-            float* ps = part + ((size_t)h * kMaxSplits + split) * DP;
-            ps[e] = o;
-            if (e == 0) { ps[D] = mt; ps[D + 1] = lt; }
-        }
-    }
-    if (S == 1) return;
-
-    // ---- split-KV: the last block of the row to arrive merges the S partials
-    __threadfence();
-    __syncthreads();
-    int32_t* counter = P.dev.counters + (size_t)bl * P.Hkv + hkv;
-    if (tid == 0) sLast = (atomicAdd(counter, 1) == S - 1) ? 1 : 0;
-    __syncthreads();
-    if (!sLast) return;
-    __threadfence();
-    for (int x = tid; x < G * D; x += 256) {
-        const int h = x / D, e = x % D;
-        const float* ph = part + (size_t)h * kMaxSplits * DP;
-        float mt = -INFINITY;
-        for (int s2 = 0; s2 < S; ++s2) mt = fmaxf(mt, ph[s2 * DP + D]);
-        float o = 0.f, lt = 0.f;
-        for (int s2 = 0; s2 < S; ++s2) {
-            const float ms = ph[s2 * DP + D];
-            const float wgt = (ms > -INFINITY) ? exp2_fast(ms - mt) : 0.f;
-            o = fmaf(ph[s2 * DP + e], wgt, o);
-            lt = fmaf(ph[s2 * DP + D + 1], wgt, lt);
+        const float* ph = part + h * DP;
+        // online merge: one round trip of independent loads instead of a max pass and a sum pass
+        float mt = -INFINITY, o = 0.f, lt = 0.f;
+        for (int s = 0; s < nu; ++s) {
+            const float* p = ph + (size_t)s * UNIT;
+            const float ms = COHERENT ? load_agent(p + D) : p[D];
+            const float ls = COHERENT ? load_agent(p + D + 1) : p[D + 1];
+            const float os = COHERENT ? load_agent(p + e) : p[e];
+            const float mn = fmaxf(mt, ms);
+            const float wo = (mt > -INFINITY) ? exp2_fast(mt - mn) : 0.f;
+            const float wn = (ms > -INFINITY) ? exp2_fast(ms - mn) : 0.f;
+            o = o * wo + os * wn;
+            lt = lt * wo + ls * wn;
+            mt = mn;
         }
         Elem<T>::store(outp + x, o / lt);
     }
-    if (tid == 0) *counter = 0;                 // ready for the next launch on this stream
 }
 
-template <typename T, int D, int G>
-hipError_t launch_one(const DecodeParams& P, int rows, hipStream_t st) {
-    decode_kernel<T, D, G><<<rows * P.S, 256, 0, st>>>(P);
+// Sum of G values over the 16 lanes of a DPP row, scattered: lane c ends up with the total of
+// head (c >> 2) & 3 (for G <= 4) -- 11 operations instead of 16 for four separate all-reduces.
+template <int G>
+__device__ __forceinline__ float row16_reduce_scatter(const float (&v)[G], int c) {
+    static_assert(G <= 4, "scatter form covers up to four heads");
+    const bool hi8 = (c & 8) != 0, hi4 = (c & 4) != 0;
+    // distance 8: lanes with bit 3 clear keep heads {0,1}, the others heads {2,3}
+    const float v0 = v[0], v1 = G > 1 ? v[1] : 0.f, v2 = G > 2 ? v[2] : 0.f, v3 = G > 3 ? v[3] : 0.f;
+    const float keepA = hi8 ? v2 : v0, sendA = hi8 ? v0 : v2;
+    const float keepB = hi8 ? v3 : v1, sendB = hi8 ? v1 : v3;
+    const float a = keepA + dpp_mov<kDppRowRor(8)>(sendA);
+    const float b = keepB + dpp_mov<kDppRowRor(8)>(sendB);
+    // bit 2 picks between the two heads still held; the half-row mirror pairs lane c with c^7
+    const float keep = hi4 ? b : a, send = hi4 ? a : b;
+    float r = keep + dpp_mov<kDppRowHalfMirror>(send);  // partner c^7: other value of bit 2, same bit 3
+    // the two quads of a half-row now hold complementary lanes: finish with sums inside the quad
+    r += dpp_mov<kDppQuadPerm(2, 3, 0, 1)>(r);
+    r += dpp_mov<kDppQuadPerm(1, 0, 3, 2)>(r);
+    return r;                                           // total of head 2*bit3 + bit2
+}
+
+// Max / sum over the 64 lanes of a wave from a DPP row all-reduce plus four lane reads.
+__device__ __forceinline__ float lane_value(float x, int l) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+__device__ __forceinline__ float wave_max_dpp(float x) {
+    x = fmaxf(x, dpp_mov<kDppRowRor(8)>(x));
+    x = fmaxf(x, dpp_mov<kDppRowRor(4)>(x));
+    x = fmaxf(x, dpp_mov<kDppRowRor(2)>(x));
+    x = fmaxf(x, dpp_mov<kDppRowRor(1)>(x));
+    return fmaxf(fmaxf(lane_value(x, 0), lane_value(x, 16)), fmaxf(lane_value(x, 32), lane_value(x, 48)));
+}
+__device__ __forceinline__ float wave_sum_dpp(float x) {
+    x = group_allreduce_sum<16>(x);
+    return (lane_value(x, 0) + lane_value(x, 16)) + (lane_value(x, 32) + lane_value(x, 48));
+}
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+template <typename T> struct IsBf16 { static constexpr bool value = false; };
+template <> struct IsBf16<bf16_t> { static constexpr bool value = true; };
+
+template <typename T, int D, int G, int NT>
+__global__ __launch_bounds__(256, (G <= 4 && NT == 1 ? 3 : 2)) void decode_kernel(DecodeParams P) {
+    constexpr bool BF = IsBf16<T>::value;
+    constexpr int EP = Elem<T>::kPer16B;        // elements in a 16-byte chunk
+    constexpr int LPR = D / EP;                 // lanes per K/V row
+    constexpr int KPI = 64 / LPR;               // rows per wave load
+    constexpr int TK = 32;                      // slots per tile
+    constexpr int NIT = TK / KPI;               // loads per tile and operand
+    constexpr int GP = pad_pow2(G);
+    constexpr int HR = (GP + 3) / 4;            // heads per 16-lane row in the softmax step
+    constexpr int KK = TK / 16;                 // slots per lane in the softmax step
+    constexpr int DP = D + 2;
+    constexpr int BK = 4 * NT * TK;             // slots per block-unit
+    constexpr bool SCATTER = (LPR == 16 && G <= 4);
+    static_assert(G <= LPR, "one lane per head needed when parking logits");
+    static_assert(NIT % 2 == 0, "P.V pairs consecutive loads");
+
+    __shared__ __align__(16) float sL[4][TK][GP];        // logits, then fp32 probabilities (fp32 path)
+    __shared__ __align__(16) uint32_t sPk[4][TK / 2][GP]; // bf16 probability pairs of loads (2i, 2i+1)
+    __shared__ float sMerge[4][G][DP];
+    __shared__ int sLast;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int sub = lane / LPR, c = lane % LPR;
+    const int srow = lane >> 4, scol = lane & 15;
+    const bool appending = P.k_new != nullptr;
+    const int w_begin = P.dev.layer_item_start[P.layer_begin];
+    const int w_end = P.dev.layer_item_start[P.layer_begin + P.n_layers];
+
+    // One block-unit per block; the hardware dispatcher balances the ragged units.  The grid is a
+    // host-side upper bound on the units of the layer range, surplus blocks leave here.
+    const int w = w_begin + blockIdx.x;
+    if (w >= w_end) return;
+    {
+        const WorkItem itv = P.dev.items[w];
+        const int kept = uniform(itv.kept), key0 = uniform(itv.key0), row_abs = uniform(itv.row_abs);
+        const int unit = uniform(itv.unit), ib = uniform(itv.b), il = uniform(itv.l);
+        const int64_t kbase = uniform64(itv.kbase), idx_base = uniform64(itv.idx_base);
+        const int lr = il - P.layer_begin;
+        const int hkv = row_abs % P.Hkv;
+        T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + ib) * P.Hq + (size_t)hkv * G) * D;
+        if (kept == 0) {                        // request rejected at compaction: defined output, no reads
+            for (int x = tid; x < G * D; x += 256) Elem<T>::store(outp + x, 0.f);
+            return;
+        }
+        const int len = kept + P.appended + (appending ? 1 : 0);
+        if (key0 >= len) return;                // unit reserved for later appends
+        const int nu = (len + BK - 1) / BK;     // units of this row that hold slots now
+        const int cap = kept + P.T_max;
+        const int new_slot = appending ? len - 1 : -1;
+        const T* Kbase = reinterpret_cast<const T*>(P.dev.kv) + kbase;
+        const T* Vbase = Kbase + (int64_t)P.Hkv * cap * D;
+        const T* knew = reinterpret_cast<const T*>(P.k_new) + ((size_t)(lr * P.B + ib) * P.Hkv + hkv) * D;
+        const T* vnew = reinterpret_cast<const T*>(P.v_new) + ((size_t)(lr * P.B + ib) * P.Hkv + hkv) * D;
+        const float scale2 = (P.sm_scale ? P.sm_scale[il] : P.default_scale) * kLog2e;
+
+        uint4 qv[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+            qv[h] = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.q) +
+                                                    ((size_t)(lr * P.B + ib) * P.Hq + (size_t)hkv * G + h) * D + c * EP);
+
+        // running max / sum live per 16-lane row: row r owns heads r*HR .. r*HR + HR - 1
+        float m_run[HR], l_run[HR], acc[G][EP];
+#pragma unroll
+        for (int hh = 0; hh < HR; ++hh) { m_run[hh] = -INFINITY; l_run[hh] = 0.f; }
+#pragma unroll
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+            for (int e = 0; e < EP; ++e) acc[h][e] = 0.f;
+
+        // K and V of a tile sit in separate register buffers.  The K loads of the next tile are issued
+        // as soon as the logits have consumed the current ones, the V loads as soon as P.V is done, so
+        // a wave keeps 8 to 16 KB in flight while it computes.
+        uint4 kb[NIT], vb[NIT];
+        auto load_row = [&](auto fullc, const T* base, const T* fresh, int t0, int i) -> uint4 {
+            constexpr bool FULL = decltype(fullc)::value;
+            if constexpr (FULL) {
+                return *reinterpret_cast<const uint4*>(base + (int64_t)(t0 + i * KPI + sub) * D + c * EP);
+            } else {
+                const int key = t0 + i * KPI + sub;
+                const T* src = (key == new_slot) ? fresh : base + (int64_t)key * D;
+                return (key < len) ? *reinterpret_cast<const uint4*>(src + c * EP) : make_uint4(0, 0, 0, 0);
+            }
+        };
+        auto issue_k = [&](int t0) {
+            const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);   // wave-uniform
+#pragma unroll
+            for (int i = 0; i < NIT; ++i)
+                kb[i] = full ? load_row(std::true_type{}, Kbase, knew, t0, i) : load_row(std::false_type{}, Kbase, knew, t0, i);
+        };
+        auto issue_v = [&](int t0) {
+            const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);
+#pragma unroll
+            for (int i = 0; i < NIT; ++i)
+                vb[i] = full ? load_row(std::true_type{}, Vbase, vnew, t0, i) : load_row(std::false_type{}, Vbase, vnew, t0, i);
+        };
+        auto tile_body = [&](auto fullc, int t0, bool more) {
+            constexpr bool FULL = decltype(fullc)::value;
+            // ---- logits of 32 slots -> LDS
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+                const int key = t0 + i * KPI + sub;
+                const bool live = FULL || key < len;
+                float part[G];
+#pragma unroll
+                for (int h = 0; h < G; ++h) part[h] = dot16<T>(kb[i], qv[h], 0.f);
+                if constexpr (SCATTER) {
+                    const float tot = row16_reduce_scatter<G>(part, c);
+                    const int hh = ((c >> 3) << 1) | ((c >> 2) & 1);
+                    if ((c & 3) == 0 && hh < G) sL[wave][i * KPI + sub][hh] = live ? tot * scale2 : -INFINITY;
+                } else {
+                    float mine = 0.f;
+#pragma unroll
+                    for (int h = 0; h < G; ++h) {
+                        const float tot = group_allreduce_sum<LPR>(part[h]);
+                        mine = (c == h) ? tot : mine;
+                    }
+                    if (c < G) sL[wave][i * KPI + sub][c] = live ? mine * scale2 : -INFINITY;
+                }
+            }
+            if (more) issue_k(t0 + TK);
+            __builtin_amdgcn_wave_barrier();
+            // ---- softmax bookkeeping: 16-lane row r handles heads r*HR.., lane column j slots j, j+16
+            float corr_row[HR];
+#pragma unroll
+            for (int hh = 0; hh < HR; ++hh) {
+                const int h = srow * HR + hh;
+                float x[KK], mt = -INFINITY;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    x[kk] = (h < G) ? sL[wave][scol + 16 * kk][h % GP] : -INFINITY;
+                    mt = fmaxf(mt, x[kk]);
+                }
+                mt = fmaxf(mt, dpp_mov<kDppRowRor(8)>(mt));
+                mt = fmaxf(mt, dpp_mov<kDppRowRor(4)>(mt));
+                mt = fmaxf(mt, dpp_mov<kDppRowRor(2)>(mt));
+                mt = fmaxf(mt, dpp_mov<kDppRowRor(1)>(mt));
+                const float m_new = fmaxf(m_run[hh], mt);            // finite for real heads: the tile holds >= 1 slot
+                float ps = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const float pr = exp2_fast(x[kk] - m_new);
+                    ps += pr;
+                    if (h < G) {
+                        const int slot = scol + 16 * kk, li = slot / KPI, ls = slot % KPI;
+                        if constexpr (BF) {
+                            // bf16 probability into its half of the pair word of loads (li & ~1, li | 1)
+                            const __bf16 pb = (__bf16)pr;
+                            reinterpret_cast<uint16_t*>(&sPk[wave][(li >> 1) * KPI + ls][h % GP])[li & 1] =
+                                __builtin_bit_cast(uint16_t, pb);
+                        } else {
+                            sL[wave][slot][h % GP] = pr;
+                        }
+                    }
+                }
+                ps = group_allreduce_sum<16>(ps);
+                corr_row[hh] = exp2_fast(m_run[hh] - m_new);
+                l_run[hh] = l_run[hh] * corr_row[hh] + ps;
+                m_run[hh] = m_new;
+            }
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+                const float ch = lane_value(corr_row[h % HR], 16 * (h / HR));
+#pragma unroll
+                for (int e = 0; e < EP; ++e) acc[h][e] *= ch;
+            }
+            __builtin_amdgcn_wave_barrier();
+            // ---- P.V
+            if constexpr (BF) {
+#pragma unroll
+                for (int i = 0; i < NIT; i += 2) {
+                    const uint32_t* pp = &sPk[wave][(i >> 1) * KPI + sub][0];
+                    uint32_t pk[G];
+#pragma unroll
+                    for (int h = 0; h < G; ++h) pk[h] = pp[h];
+                    const uint32_t a[4] = {vb[i].x, vb[i].y, vb[i].z, vb[i].w};
+                    const uint32_t b[4] = {vb[i + 1].x, vb[i + 1].y, vb[i + 1].z, vb[i + 1].w};
+#pragma unroll
+                    for (int d2 = 0; d2 < 4; ++d2) {
+                        const uint32_t lo = __builtin_amdgcn_perm(b[d2], a[d2], 0x05040100u);   // (a.even, b.even)
+                        const uint32_t hi = __builtin_amdgcn_perm(b[d2], a[d2], 0x07060302u);   // (a.odd,  b.odd)
+#pragma unroll
+                        for (int h = 0; h < G; ++h) {
+                            acc[h][2 * d2] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, lo), __builtin_bit_cast(bf16x2_t, pk[h]), acc[h][2 * d2], false);
+                            acc[h][2 * d2 + 1] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, hi), __builtin_bit_cast(bf16x2_t, pk[h]), acc[h][2 * d2 + 1], false);
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NIT; ++i) {
+                    float f[EP];
+                    unpack16(vb[i], f, (const T*)nullptr);
+                    const float* pp = &sL[wave][i * KPI + sub][0];
+#pragma unroll
+                    for (int h = 0; h < G; ++h) {
+                        const float ph = pp[h];
+#pragma unroll
+                        for (int e = 0; e < EP; ++e) acc[h][e] = fmaf(ph, f[e], acc[h][e]);
+                    }
+                }
+            }
+            if (more) issue_v(t0 + TK);
+            __builtin_amdgcn_wave_barrier();
+        };
+        const int tw0 = key0 + wave * NT * TK;  // first slot of this wave
+        if (tw0 < len) { issue_k(tw0); issue_v(tw0); }
+#pragma unroll 1
+        for (int t = 0; t < NT; ++t) {
+            const int t0 = tw0 + t * TK;
+            if (t0 >= len) break;               // wave-uniform
+            const bool more = (t + 1 < NT) && (t0 + TK < len);
+            const bool full = (t0 + TK <= len);
+            if (full) tile_body(std::true_type{}, t0, more); else tile_body(std::false_type{}, t0, more);
+        }
+
+        // The unit that holds the new slot also stores the new row into the cache.
+        if (appending && new_slot >= key0 && new_slot < key0 + BK && wave == 0 && sub == 0) {
+            T* kdst = const_cast<T*>(Kbase) + (int64_t)new_slot * D;
+            T* vdst = const_cast<T*>(Vbase) + (int64_t)new_slot * D;
+            *reinterpret_cast<uint4*>(kdst + c * EP) = *reinterpret_cast<const uint4*>(knew + c * EP);
+            *reinterpret_cast<uint4*>(vdst + c * EP) = *reinterpret_cast<const uint4*>(vnew + c * EP);
+            if (c == 0) P.dev.idx[idx_base + new_slot] = P.m + P.appended;
+        }
+
+        // ---- sum the row groups of the wave, then merge the 4 waves through LDS
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+            for (int h = 0; h < G; ++h)
+#pragma unroll
+                for (int e = 0; e < EP; ++e) acc[h][e] += __shfl_xor(acc[h][e], off, 64);
+        if (sub == 0) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) {
+#pragma unroll
+                for (int e = 0; e < EP; ++e) sMerge[wave][h][c * EP + e] = acc[h][e];
+            }
+        }
+        if (scol == 0) {
+#pragma unroll
+            for (int hh = 0; hh < HR; ++hh)
+                if (srow * HR + hh < G) {
+                    sMerge[wave][srow * HR + hh][D] = m_run[hh];
+                    sMerge[wave][srow * HR + hh][D + 1] = l_run[hh];
+                }
+        }
+        __syncthreads();
+        float* part = P.dev.partials + (size_t)w * G * DP;
+        for (int x = tid; x < G * D; x += 256) {
+            const int h = x / D, e = x % D;
+            float mt = -INFINITY;
+#pragma unroll
+            for (int wv = 0; wv < 4; ++wv) mt = fmaxf(mt, sMerge[wv][h][D]);
+            float o = 0.f, lt = 0.f;
+#pragma unroll
+            for (int wv = 0; wv < 4; ++wv) {
+                const float mw = sMerge[wv][h][D];
+                const float wgt = (mw > -INFINITY) ? exp2_fast(mw - mt) : 0.f;
+                o = fmaf(sMerge[wv][h][e], wgt, o);
+                lt = fmaf(sMerge[wv][h][D + 1], wgt, lt);
+            }
+            if (nu == 1) {
+                Elem<T>::store(outp + x, o / lt);
+            } else if (P.merge_mode == 1) {
+                store_agent(part + h * DP + e, o);
+                if (e == 0) { store_agent(part + h * DP + D, mt); store_agent(part + h * DP + D + 1, lt); }
+            } else {
+                part[h * DP + e] = o;
+                if (e == 0) { part[h * DP + D] = mt; part[h * DP + D + 1] = lt; }
+            }
+        }
+        if (nu > 1 && P.merge_mode == 1) {
+            // The barrier waits for this block's device-scope stores to complete; the counter then
+            // publishes them.  The unit that counts nu - 1 predecessors merges.
+            __syncthreads();
+            int32_t* counter = P.dev.counters + row_abs;
+            if (tid == 0)
+                sLast = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nu - 1) ? 1 : 0;
+            __syncthreads();
+            if (sLast) {
+                merge_partials<T, D, G, true>(P.dev.partials + (size_t)(w - unit) * G * DP, outp, nu, tid);
+                if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+// Second kernel of merge mode 2: one block per (layer, request, KV head) row.
+template <typename T, int D, int G, int NT>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
+    constexpr int BK = 4 * NT * 32;
+    const int row = blockIdx.x;
+    const int hkv = row % P.Hkv;
+    const int b = (row / P.Hkv) % P.B;
+    const int lr = row / (P.Hkv * P.B);
+    const int bl = b * P.L + P.layer_begin + lr;
+    const int kept = P.dev.kept[bl];
+    if (kept == 0) return;
+    const int len = kept + P.appended + (P.k_new ? 1 : 0);
+    const int nu = (len + BK - 1) / BK;
+    if (nu == 1) return;
+    T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + b) * P.Hq + (size_t)hkv * G) * D;
+    const int w0 = P.dev.row_item_first[(size_t)bl * P.Hkv + hkv];
+    merge_partials<T, D, G, false>(P.dev.partials + (size_t)w0 * G * (D + 2), outp, nu, threadIdx.x);
+}
+
+template <typename T, int D, int G, int NT>
+hipError_t launch_nt(const DecodeParams& P, int grid, int rows, hipStream_t st) {
+    decode_kernel<T, D, G, NT><<<grid, 256, 0, st>>>(P);
+    if (P.merge_mode == 2) decode_merge_kernel<T, D, G, NT><<<rows, 256, 0, st>>>(P);
     return hipGetLastError();
 }
 
+template <typename T, int D, int G>
+hipError_t launch_one(const DecodeParams& P, int nt, int grid, int rows, hipStream_t st) {
+    if (nt == 1) return launch_nt<T, D, G, 1>(P, grid, rows, st);
+    if (nt == 2) return launch_nt<T, D, G, 2>(P, grid, rows, st);
+    return launch_nt<T, D, G, 4>(P, grid, rows, st);
+}
+
 template <typename T, int D>
-hipError_t launch_g(const DecodeParams& P, int g, int rows, hipStream_t st) {
+hipError_t launch_g(const DecodeParams& P, int g, int nt, int grid, int rows, hipStream_t st) {
     switch (g) {
-        case 1: return launch_one<T, D, 1>(P, rows, st);
-        case 2: return launch_one<T, D, 2>(P, rows, st);
-        case 3: return launch_one<T, D, 3>(P, rows, st);
-        case 4: return launch_one<T, D, 4>(P, rows, st);
-        case 5: return launch_one<T, D, 5>(P, rows, st);
-        case 6: return launch_one<T, D, 6>(P, rows, st);
-        case 7: return launch_one<T, D, 7>(P, rows, st);
-        case 8: return launch_one<T, D, 8>(P, rows, st);
+        case 1: return launch_one<T, D, 1>(P, nt, grid, rows, st);
+        case 2: return launch_one<T, D, 2>(P, nt, grid, rows, st);
+        case 3: return launch_one<T, D, 3>(P, nt, grid, rows, st);
+        case 4: return launch_one<T, D, 4>(P, nt, grid, rows, st);
+        case 5: return launch_one<T, D, 5>(P, nt, grid, rows, st);
+        case 6: return launch_one<T, D, 6>(P, nt, grid, rows, st);
+        case 7: return launch_one<T, D, 7>(P, nt, grid, rows, st);
+        case 8: return launch_one<T, D, 8>(P, nt, grid, rows, st);
     }
     return hipErrorInvalidValue;
+}
+
+int env_int(const char* name, int dflt) {
+    const char* e = getenv(name);
+    return e ? atoi(e) : dflt;
 }
 
 }  // namespace
@@ -281,22 +495,22 @@ hipError_t launch_decode(const DecodeArgs& a) {
     P.q = a.q; P.k_new = a.k_new; P.v_new = a.v_new; P.out = a.out; P.sm_scale = a.sm_scale;
     P.dev = c.dev;
     P.B = s.B; P.L = s.L; P.Hq = s.Hq; P.Hkv = s.Hkv; P.m = s.m;
-    P.layer_begin = a.layer_begin; P.T_max = c.T_max;
+    P.layer_begin = a.layer_begin; P.n_layers = a.n_layers; P.T_max = c.T_max;
     P.appended = a.appended;
     P.default_scale = 1.0f / sqrtf((float)s.d);
+    P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knob
     const int rows = a.n_layers * s.B * s.Hkv;
-    // Split-KV factor from what the host knows: the mean budget bound and the step count.
-    const int64_t est_len = c.sum_k_max / s.L + a.appended + 1;
-    const int ntiles = (int)((est_len + 63) / 64);
-    int waves_per_row = (4096 + rows - 1) / rows;
-    if (waves_per_row > ntiles) waves_per_row = ntiles;
-    int S = (waves_per_row + 3) / 4;
-    if (S < 1) S = 1;
-    if (S > kMaxSplits) S = kMaxSplits;
-    P.S = S;
+    // Upper bound on the block-units of the layer range: every row at the full prompt length, and
+    // never more than the whole work list.
+    const int64_t bk = c.unit_slots;
+    int64_t grid = (int64_t)rows * (((int64_t)s.m + c.T_max + bk - 1) / bk);
+    if (grid > c.max_items) grid = c.max_items;
+    if (grid < 1) grid = 1;
     const int g = s.Hq / s.Hkv;
-    if (s.dtype == VLC_F32) return s.d == 64 ? launch_g<float, 64>(P, g, rows, a.stream) : launch_g<float, 128>(P, g, rows, a.stream);
-    return s.d == 64 ? launch_g<bf16_t, 64>(P, g, rows, a.stream) : launch_g<bf16_t, 128>(P, g, rows, a.stream);
+    const int nt = (int)(bk / 128);
+    if (s.dtype == VLC_F32)
+        return s.d == 64 ? launch_g<float, 64>(P, g, nt, (int)grid, rows, a.stream) : launch_g<float, 128>(P, g, nt, (int)grid, rows, a.stream);
+    return s.d == 64 ? launch_g<bf16_t, 64>(P, g, nt, (int)grid, rows, a.stream) : launch_g<bf16_t, 128>(P, g, nt, (int)grid, rows, a.stream);
 }
 
 }  // namespace vlc

@@ -10,9 +10,23 @@
 
 namespace vlc {
 
-constexpr int kMaxSplits = 16;         // split-KV blocks per (b, l, kv head) row of decode
 constexpr int kMaxLayers = 1024;
 constexpr int kScoreChunk = 256;       // keys per block of the generic scoring sweeps
+
+// One block-unit of decode work: `unit_slots` consecutive cache slots of one (b, l, kv head) row.
+// Built on the device by vlc_topk_compact, ordered by (layer, request, kv head, unit) so that a
+// layer range is a contiguous slice of the list.
+struct WorkItem {
+    int32_t row_abs;                   // (b*L + l)*Hkv + hkv
+    int32_t key0;                      // first slot of the unit
+    int32_t kept;                      // validated k[b][l]; 0 marks a rejected row
+    int32_t unit;                      // index of the unit inside its row
+    int64_t kbase;                     // element offset of the row's K slab inside the kv region
+    int64_t idx_base;                  // offset of the row's kept-index list inside the idx region
+    int32_t b, l;
+    int32_t pad[2];
+};
+static_assert(sizeof(WorkItem) == 48, "WorkItem layout");
 
 struct CacheDev {                      // device pointers into the caller's arena
     int32_t* status;                   // [4]
@@ -20,7 +34,10 @@ struct CacheDev {                      // device pointers into the caller's aren
     int32_t* kept;                     // [B*L]
     char* kv;
     int32_t* idx;
-    float* partials;                   // [B*L*Hq][kMaxSplits][d + 2]
+    WorkItem* items;                   // [max_items]
+    int32_t* layer_item_start;         // [L+1]
+    int32_t* row_item_first;           // [B*L*Hkv]
+    float* partials;                   // [max_items][g][d + 2]
     int32_t* counters;                 // [B*L*Hkv]
 };
 
@@ -31,6 +48,8 @@ struct vlc_cache {
     int32_t T_max;
     int64_t sum_k_max;
     int64_t slots_per_request;
+    int32_t unit_slots;                // slots per decode block-unit (128, 256 or 512)
+    int64_t max_items;
     char* arena;
     vlc_cache_layout layout;
     vlc::CacheDev dev;

@@ -11,37 +11,78 @@
 namespace vlc {
 namespace {
 
-__global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, int L, int Hkv, int m,
-                                                     int T_max, int64_t slots_per_request, CacheDev dev) {
-    __shared__ int32_t kept_s[kMaxLayers];
-    __shared__ int64_t pre[kMaxLayers];
-    __shared__ int bad;
-    const int b = blockIdx.x;
-    if (threadIdx.x == 0) bad = 0;
-    for (int l = threadIdx.x; l < L; l += blockDim.x) {
-        int kk = k[(size_t)b * L + l];
+// One block for the whole batch (B*L is a few hundred entries): validates the budgets, lays the
+// slabs of each request out back to back, and builds the decode work list.
+__global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, int B, int L, int Hkv, int m,
+                                                     int d, int T_max, int64_t slots_per_request, int unit_slots,
+                                                     int64_t max_items, CacheDev dev) {
+    __shared__ int bad[64];
+    const int tid = threadIdx.x;
+    // budgets in range?
+    for (int x = tid; x < B * L; x += blockDim.x) {
+        int kk = k[x];
         if (kk < 1 || kk > m) {
-            set_sticky(dev.status, VLC_ERR_INVALID_ARG, b, l, kk);
+            set_sticky(dev.status, VLC_ERR_INVALID_ARG, x / L, x % L, kk);
             kk = 0;
         }
-        kept_s[l] = kk;
+        dev.kept[x] = kk;
     }
+    for (int x = tid; x < B * L * Hkv; x += blockDim.x) dev.counters[x] = 0;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    // slab offsets, one thread per request; a request whose budgets do not fit keeps nothing
+    for (int b = tid; b < B; b += blockDim.x) {
         int64_t acc = 0;
-        for (int l = 0; l < L; ++l) { pre[l] = acc; acc += kept_s[l] + T_max; }
-        if (acc > slots_per_request) {
-            set_sticky(dev.status, VLC_ERR_CAPACITY, b, -1, (int)min(acc, (int64_t)INT32_MAX));
-            bad = 1;
+        for (int l = 0; l < L; ++l) acc += dev.kept[b * L + l] + T_max;
+        const bool over = acc > slots_per_request;
+        if (over) set_sticky(dev.status, VLC_ERR_CAPACITY, b, -1, (int)min(acc, (int64_t)INT32_MAX));
+        acc = 0;
+        for (int l = 0; l < L; ++l) {
+            if (over) dev.kept[b * L + l] = 0;
+            dev.slot_off[b * L + l] = (int64_t)b * slots_per_request + acc;
+            acc += dev.kept[b * L + l] + T_max;
         }
     }
     __syncthreads();
-    for (int l = threadIdx.x; l < L; l += blockDim.x) {
-        // a request whose budgets do not fit keeps nothing: every later kernel skips its rows
-        dev.slot_off[(size_t)b * L + l] = (int64_t)b * slots_per_request + (bad ? (int64_t)l * T_max : pre[l]);
-        dev.kept[(size_t)b * L + l] = bad ? 0 : kept_s[l];
+    // work list: units per row, prefix over (layer, request)
+    if (tid == 0) {
+        int64_t acc = 0;
+        for (int l = 0; l < L; ++l) {
+            dev.layer_item_start[l] = (int)acc;
+            for (int b = 0; b < B; ++b) {
+                const int kk = dev.kept[b * L + l];
+                const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
+                for (int h = 0; h < Hkv; ++h) dev.row_item_first[(size_t)(b * L + l) * Hkv + h] = (int)(acc + (int64_t)h * nu);
+                acc += (int64_t)nu * Hkv;
+            }
+        }
+        dev.layer_item_start[L] = (int)acc;
+        bad[0] = acc > max_items;       // cannot happen for budgets that passed the capacity check
     }
-    for (int x = threadIdx.x; x < L * Hkv; x += blockDim.x) dev.counters[(size_t)b * L * Hkv + x] = 0;
+    __syncthreads();
+    if (bad[0]) {
+        if (tid == 0) {
+            set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
+            for (int l = 0; l <= L; ++l) dev.layer_item_start[l] = 0;
+        }
+        return;
+    }
+    for (int x = tid; x < B * L * Hkv; x += blockDim.x) {
+        const int h = x % Hkv, bl = x / Hkv, b = bl / L, l = bl % L;
+        const int kk = dev.kept[bl];
+        const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
+        const int cap = kk + T_max;
+        const int64_t so = dev.slot_off[bl];
+        WorkItem it;
+        it.row_abs = x; it.kept = kk; it.b = b; it.l = l; it.pad[0] = it.pad[1] = 0;
+        it.kbase = ((so * 2 * Hkv) + (int64_t)h * cap) * d;
+        it.idx_base = so * Hkv + (int64_t)h * cap;
+        const int w0 = dev.row_item_first[x];
+        for (int u = 0; u < nu; ++u) {
+            it.unit = u;
+            it.key0 = u * unit_slots;
+            dev.items[w0 + u] = it;
+        }
+    }
 }
 
 // Order-preserving map float -> uint32 (larger float, larger key).
@@ -202,7 +243,8 @@ hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const in
                                const void* k_full, const void* v_full, int32_t* idx_out, hipStream_t st) {
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
-    layout_kernel<<<s.B, 256, 0, st>>>(k, s.L, s.Hkv, s.m, c.T_max, c.slots_per_request, c.dev);
+    layout_kernel<<<1, 256, 0, st>>>(k, s.B, s.L, s.Hkv, s.m, s.d, c.T_max, c.slots_per_request, c.unit_slots,
+                               c.max_items, c.dev);
     select_kernel<<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, idx_out);
     const int rowbytes = s.d * (s.dtype == VLC_F32 ? 4 : 2);
     int gx = (4096 + rows - 1) / rows;
