@@ -51,12 +51,34 @@ double region_size(const vlc_shape& s) {
     return (double)s.tau * (s.m - s.tau) + (double)s.tau * (s.tau + 1) / 2.0;
 }
 
+// Workspace layout: [partial row statistics][exponent-domain row max][scratch row max][scratch row sum]
+struct WsPlan { size_t part, stats, total; bool mfma; };
+
+WsPlan ws_plan(const vlc_shape& s) {
+    WsPlan w;
+    const char* force = getenv("VLC_SCORE_PATH");             // tuning knob: "simple" forces the plain-ALU sweeps
+    w.mfma = vlc::score_mfma_supported(s) && !(force && strcmp(force, "simple") == 0);
+    const size_t a = vlc::score_simple_workspace_bytes(s), b = vlc::score_mfma_workspace_bytes(s);
+    w.part = align_up(a > b ? a : b, 256);
+    w.stats = align_up((size_t)s.B * s.L * s.Hq * s.tau * sizeof(float), 256);
+    w.total = w.part + 3 * w.stats;
+    return w;
+}
+
 vlc::ScoreArgs score_args(const vlc_shape* s, const void* q_win, const void* k, const float* sm_scale, float p,
                           float* scores, float* row_max, float* row_sum, uint64_t* nnz, void* ws, vlc_stream st) {
     vlc::ScoreArgs a;
     a.s = *s; a.q_win = q_win; a.k = k; a.sm_scale = sm_scale; a.p = p; a.scores = scores;
     a.row_max = row_max; a.row_sum = row_sum; a.nnz = nnz; a.workspace = ws; a.stream = (hipStream_t)st;
+    a.row_max_t = (float*)((char*)ws + ws_plan(*s).part);
     return a;
+}
+
+hipError_t run_rowstats(const vlc::ScoreArgs& a, bool mfma) {
+    return mfma ? vlc::launch_rowstats_mfma(a) : vlc::launch_rowstats_simple(a);
+}
+hipError_t run_colsweep(const vlc::ScoreArgs& a, bool mfma, bool have_row_max_t) {
+    return mfma ? vlc::launch_colsweep_mfma(a, have_row_max_t) : vlc::launch_colsweep_simple(a);
 }
 
 }  // namespace
@@ -68,9 +90,7 @@ const char* vlc_version(void) { return "vlcache-mi355x 0.1 (gfx950)"; }
 
 size_t vlc_workspace_bytes(const vlc_shape* shape) {
     if (check_shape(shape) != VLC_OK) return 0;
-    // partial row statistics + a private copy of the row statistics for the standalone sparsity sweep
-    const size_t stats = (size_t)shape->B * shape->L * shape->Hq * shape->tau * sizeof(float);
-    return align_up(vlc::score_simple_workspace_bytes(*shape), 256) + 2 * align_up(stats, 256);
+    return ws_plan(*shape).total;
 }
 
 vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k, const float* sm_scale, float p,
@@ -83,13 +103,14 @@ vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k, c
     if (workspace_bytes < vlc_workspace_bytes(shape))
         return fail(VLC_ERR_CAPACITY, "vlc_score: workspace of %zu bytes, %zu needed", workspace_bytes, vlc_workspace_bytes(shape));
     vlc::ScoreArgs a = score_args(shape, q_win, k, sm_scale, p, scores, row_max, row_sum, nnz, workspace, stream);
-    hipError_t e = vlc::launch_rowstats_simple(a);
+    const bool mfma = ws_plan(*shape).mfma;
+    hipError_t e = run_rowstats(a, mfma);
     if (e != hipSuccess) return hip_fail(e, "vlc_score row statistics");
     if (nnz) {
         e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, a.stream);
         if (e != hipSuccess) return hip_fail(e, "vlc_score clear counts");
     }
-    e = vlc::launch_colsweep_simple(a);
+    e = run_colsweep(a, mfma, true);
     if (e != hipSuccess) return hip_fail(e, "vlc_score column sweep");
     return VLC_OK;
 }
@@ -106,20 +127,22 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
         if (workspace_bytes < vlc_workspace_bytes(shape))
             return fail(VLC_ERR_CAPACITY, "vlc_sparsity: workspace of %zu bytes, %zu needed", workspace_bytes, vlc_workspace_bytes(shape));
         vlc::ScoreArgs a = score_args(shape, q_win, k, sm_scale, p, nullptr, nullptr, nullptr, nnz, workspace, stream);
+        const WsPlan wp = ws_plan(*shape);
+        bool have_t = false;
         if (row_max) {
             a.row_max = const_cast<float*>(row_max);
         } else {
-            const size_t stats = align_up((size_t)shape->B * shape->L * shape->Hq * shape->tau * sizeof(float), 256);
-            char* tail = (char*)workspace + align_up(vlc::score_simple_workspace_bytes(*shape), 256);
+            char* tail = (char*)workspace + wp.part + wp.stats;
             a.row_max = (float*)tail;
-            a.row_sum = (float*)(tail + stats);
-            hipError_t e = vlc::launch_rowstats_simple(a);
+            a.row_sum = (float*)(tail + wp.stats);
+            hipError_t e = run_rowstats(a, wp.mfma);
             if (e != hipSuccess) return hip_fail(e, "vlc_sparsity row statistics");
             a.row_sum = nullptr;
+            have_t = true;
         }
         hipError_t e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, hs);
         if (e != hipSuccess) return hip_fail(e, "vlc_sparsity clear counts");
-        e = vlc::launch_colsweep_simple(a);
+        e = run_colsweep(a, wp.mfma, have_t);
         if (e != hipSuccess) return hip_fail(e, "vlc_sparsity count sweep");
     }
     if (gamma) {

@@ -1,0 +1,378 @@
+// Matrix-core scoring sweeps for bf16 storage (gfx950, v_mfma_f32_32x32x16_bf16).
+//
+// The post-vision window Q' K^T of Alg. 1 is the one dense contraction of the path: per KV head a
+// (g * tau) x d x m product.  Following the two-sweep schedule of the paper's App. A.3, neither
+// the logits nor the attention matrix reach HBM:
+//   sweep 1 (row statistics) computes S^T = K Q'^T tile by tile, so that the 16 values a lane holds
+//           belong to ONE query row: running max and sum stay in the lane, with one rescale per
+//           32-key tile instead of one per element;
+//   sweep 2 (column sums + ThresholdFilter counts) computes S = Q' K^T, so that a lane holds 16
+//           query rows of ONE key: the sum over the window rows of Sec. 3.2 is in-lane too, and the
+//           Eq. 1 test is one compare on the exponent argument.
+// Q' fragments of a block's rows live in registers for the whole sweep; K streams through LDS in
+// chunks of 128 keys (global -> registers -> LDS, the next chunk in flight while the current one is
+// multiplied).  Each head's tau window rows are padded to a multiple of 32 so that every 32-row
+// block belongs to one query head; padded rows carry a +inf offset and vanish from every sum.
+#include "common.h"
+#include "internal.h"
+
+namespace vlc {
+namespace {
+
+constexpr int kD = 128;                 // head dimension of this path
+constexpr int kChunk = 128;             // keys per LDS chunk
+constexpr int kPitch = kD + 8;          // bf16 elements per LDS row (272 bytes: conflict-free 16-byte reads)
+constexpr int kKSteps = kD / 16;        // MFMA k-steps per tile
+
+struct MfmaArgs {
+    const bf16_t* q_win;
+    const bf16_t* k;
+    const float* sm_scale;
+    float2* part;            // [group][split][RP] partial (max, sum), exponent domain (log2)
+    const float* row_max;    // natural-log domain, [B,L,Hq,tau]
+    const float* row_max_t;  // same in the exponent domain, or null
+    const float* row_sum;
+    float* scores;           // may be null
+    unsigned long long* nnz; // may be null
+    float log2p;
+    int L, Hq, Hkv, g, m, tau, tauP, RP, keys_per_split, nsplit;
+};
+
+// Fragment of one operand: lane (l % 32) owns a row (or column) index, lane half l / 32 the
+// 8 consecutive k-values [16 ks + 8 half, +8).
+__device__ __forceinline__ bf16x8_t as_frag(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
+
+template <int WAVES, int RB>
+__device__ __forceinline__ void load_q_frags(const MfmaArgs& a, int bl, int hkv, int wave, int lane, uint4 (&qf)[RB][kKSteps]) {
+    const int half = lane >> 5;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int r = (wave * RB + rb) * 32 + (lane & 31);
+        const int hl = r / a.tauP, iw = r % a.tauP;
+        const bool ok = hl < a.g && iw < a.tau;
+        const bf16_t* row = a.q_win + (((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0)) * kD;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+            qf[rb][ks] = ok ? *reinterpret_cast<const uint4*>(row + ks * 16 + half * 8) : make_uint4(0, 0, 0, 0);
+    }
+}
+
+// K chunk staging: global -> registers -> LDS.  Keys at or beyond m are zero-filled.
+template <int THREADS>
+struct KStage {
+    static constexpr int N = kChunk * (kD / 8) / THREADS;      // 16-byte pieces per thread
+    uint4 r[N];
+    __device__ __forceinline__ void load(const bf16_t* kg, int key0, int m) {
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int x = threadIdx.x + THREADS * u;
+            const int row = x >> 4, piece = x & 15;
+            const int key = key0 + row;
+            r[u] = (key < m) ? *reinterpret_cast<const uint4*>(kg + (size_t)key * kD + piece * 8) : make_uint4(0, 0, 0, 0);
+        }
+    }
+    __device__ __forceinline__ void store(bf16_t* sK) const {
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const int x = threadIdx.x + THREADS * u;
+            const int row = x >> 4, piece = x & 15;
+            *reinterpret_cast<uint4*>(sK + row * kPitch + piece * 8) = r[u];
+        }
+    }
+};
+
+__device__ __forceinline__ void load_k_frags(const bf16_t* sK, int tile, int lane, uint4 (&kf)[kKSteps]) {
+    const bf16_t* row = sK + (tile * 32 + (lane & 31)) * kPitch + (lane >> 5) * 8;
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) kf[ks] = *reinterpret_cast<const uint4*>(row + ks * 16);
+}
+
+// Row index (0..31) of accumulator element i of a 32x32 MFMA tile in lane `lane`.
+__device__ __forceinline__ int acc_row(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
+
+// ------------------------------------------------------------------------------------------------
+// Sweep 1: partial row statistics of one key range of one KV group.
+template <int WAVES, int RB>
+__global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
+    constexpr int THREADS = WAVES * 64;
+    __shared__ __align__(16) bf16_t sK[kChunk * kPitch];
+    const int group = blockIdx.y, split = blockIdx.x;
+    const int hkv = group % a.Hkv, bl = group / a.Hkv, l = bl % a.L;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float c = (a.sm_scale ? a.sm_scale[l] : rsqrtf((float)kD)) * kLog2e;
+    const bf16_t* kg = a.k + (size_t)group * a.m * kD;
+    const int k_begin = split * a.keys_per_split;
+    const int k_end = min(a.m, k_begin + a.keys_per_split);
+
+    uint4 qf[RB][kKSteps];
+    load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, qf);
+    // this lane's query row per row block, and the last key it may see (causal mask of Alg. 1)
+    int jlim[RB];
+    float m_run[RB], z_run[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int r = (wave * RB + rb) * 32 + (lane & 31);
+        jlim[rb] = a.m - a.tau + (r % a.tauP);
+        m_run[rb] = -INFINITY;
+        z_run[rb] = 0.f;
+    }
+
+    KStage<THREADS> st;
+    if (k_begin < k_end) st.load(kg, k_begin, a.m);
+    for (int kc = k_begin; kc < k_end; kc += kChunk) {
+        __syncthreads();                                   // previous chunk fully consumed
+        st.store(sK);
+        __syncthreads();
+        if (kc + kChunk < k_end) st.load(kg, kc + kChunk, a.m);
+        const bool masked = kc + kChunk > a.m - a.tau + 1;     // chunk reaches past the first window key
+#pragma unroll 1
+        for (int t = 0; t < kChunk / 32; ++t) {
+            if (kc + t * 32 >= k_end) break;
+            uint4 kf[kKSteps];
+            load_k_frags(sK, t, lane, kf);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                if ((wave * RB + rb) * 32 >= a.RP) continue;       // wave-uniform: no rows here
+                f32x16_t acc = {0};
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(kf[ks]), as_frag(qf[rb][ks]), acc, 0, 0, 0);
+                // acc[i] = <k_key, q_row>, key = kc + 32 t + acc_row(i), row = this lane's
+                float v[16];
+                if (masked) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) v[i] = (kc + t * 32 + acc_row(i, lane) <= jlim[rb]) ? acc[i] : -INFINITY;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) v[i] = acc[i];
+                }
+                float tmax = v[0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, v[i]);
+                const float m_new = fmaxf(m_run[rb], tmax * c);
+                if (m_new > -INFINITY) {
+                    float zs = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) zs += exp2_fast(fmaf(v[i], c, -m_new));
+                    z_run[rb] = z_run[rb] * exp2_fast(m_run[rb] - m_new) + zs;
+                    m_run[rb] = m_new;
+                }
+            }
+        }
+    }
+    // the two lane halves hold disjoint keys of the same query row
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const float mo = __shfl_xor(m_run[rb], 32, 64), zo = __shfl_xor(z_run[rb], 32, 64);
+        const float mm = fmaxf(m_run[rb], mo);
+        float z = 0.f;
+        if (m_run[rb] > -INFINITY) z += z_run[rb] * exp2_fast(m_run[rb] - mm);
+        if (mo > -INFINITY) z += zo * exp2_fast(mo - mm);
+        const int r = (wave * RB + rb) * 32 + (lane & 31);
+        if (lane < 32 && r < a.RP) a.part[((size_t)group * a.nsplit + split) * a.RP + r] = make_float2(mm, z);
+    }
+}
+
+// Merge the per-split partials: one thread per (group, padded row).  Writes the natural-log row
+// max and the row sum in the caller's [B,L,Hq,tau] layout and the exponent-domain max for sweep 2.
+__global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
+                                           float* __restrict__ row_sum, float* __restrict__ row_max_t,
+                                           int groups, int nsplit, int RP, int tauP, int tau, int g, int Hq, int Hkv) {
+    const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= (size_t)groups * RP) return;
+    const int r = (int)(x % RP), group = (int)(x / RP);
+    const int hl = r / tauP, iw = r % tauP;
+    if (hl >= g || iw >= tau) return;
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part[((size_t)group * nsplit + s) * RP + r].x);
+    float Z = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float2 p = part[((size_t)group * nsplit + s) * RP + r];
+        if (p.x > -INFINITY) Z += p.y * exp2_fast(p.x - M);
+    }
+    const int hkv = group % Hkv, bl = group / Hkv;
+    const size_t o = ((size_t)bl * Hq + (size_t)hkv * g + hl) * tau + iw;
+    row_max[o] = M * kLn2;
+    row_sum[o] = Z;
+    row_max_t[o] = M;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sweep 2: column sums of the softmax over all window rows of the KV group, and per-head counts.
+template <int WAVES, int RB>
+__global__ __launch_bounds__(WAVES * 64) void colsweep_mfma_kernel(MfmaArgs a) {
+    constexpr int THREADS = WAVES * 64;
+    __shared__ __align__(16) bf16_t sK[kChunk * kPitch];
+    __shared__ float sCol[WAVES][kChunk];
+    const int group = blockIdx.y, split = blockIdx.x;
+    const int hkv = group % a.Hkv, bl = group / a.Hkv, l = bl % a.L;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float c = (a.sm_scale ? a.sm_scale[l] : rsqrtf((float)kD)) * kLog2e;
+    const bf16_t* kg = a.k + (size_t)group * a.m * kD;
+    const int k_begin = split * a.keys_per_split;
+    const int k_end = min(a.m, k_begin + a.keys_per_split);
+
+    uint4 qf[RB][kKSteps];
+    load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, qf);
+    // per accumulator slot: exponent offset (+inf for padded rows) and 1 / row sum
+    float mc[RB][16], iz[RB][16];
+    uint32_t cnt[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        cnt[rb] = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int r = (wave * RB + rb) * 32 + acc_row(i, lane);
+            const int hl = r / a.tauP, iw = r % a.tauP;
+            const bool ok = hl < a.g && iw < a.tau;
+            const size_t o = ((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0);
+            const float mt = a.row_max_t ? a.row_max_t[o] : a.row_max[o] * kLog2e;
+            mc[rb][i] = ok ? mt : INFINITY;
+            iz[rb][i] = (ok && a.row_sum) ? 1.f / a.row_sum[o] : 0.f;
+        }
+    }
+
+    KStage<THREADS> st;
+    if (k_begin < k_end) st.load(kg, k_begin, a.m);
+    for (int kc = k_begin; kc < k_end; kc += kChunk) {
+        __syncthreads();
+        st.store(sK);
+        __syncthreads();
+        if (kc + kChunk < k_end) st.load(kg, kc + kChunk, a.m);
+        const bool masked = kc + kChunk > a.m - a.tau + 1;
+#pragma unroll 1
+        for (int t = 0; t < kChunk / 32; ++t) {
+            uint4 kf[kKSteps];
+            load_k_frags(sK, t, lane, kf);
+            const int key = kc + t * 32 + (lane & 31);          // this lane's key (column of the tile)
+            float col = 0.f;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                if ((wave * RB + rb) * 32 >= a.RP) continue;
+                f32x16_t acc = {0};
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(qf[rb][ks]), as_frag(kf[ks]), acc, 0, 0, 0);
+                // acc[i] = <q_row, k_key>, row = row block base + acc_row(i), key = this lane's
+                if (masked) {
+                    const int base = a.m - a.tau + ((wave * RB + rb) * 32) % a.tauP;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const bool valid = key <= base + acc_row(i, lane);
+                        const float ea = fmaf(acc[i], c, -mc[rb][i]);
+                        const float e = valid ? exp2_fast(ea) : 0.f;
+                        col = fmaf(e, iz[rb][i], col);
+                        cnt[rb] += (valid && ea >= a.log2p) ? 1u : 0u;
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float ea = fmaf(acc[i], c, -mc[rb][i]);
+                        col = fmaf(exp2_fast(ea), iz[rb][i], col);
+                        cnt[rb] += (ea >= a.log2p) ? 1u : 0u;
+                    }
+                }
+            }
+            col += __shfl_xor(col, 32, 64);                     // the lane halves hold different rows of the same key
+            if (lane < 32) sCol[wave][t * 32 + lane] = col;
+        }
+        __syncthreads();
+        if (a.scores && threadIdx.x < kChunk && kc + threadIdx.x < k_end) {
+            float s = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) s += sCol[w][threadIdx.x];
+            a.scores[(size_t)group * a.m + kc + threadIdx.x] = s;
+        }
+    }
+    if (a.nnz) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int rbase = (wave * RB + rb) * 32;
+            if (rbase >= a.RP) continue;
+            const uint32_t tot = wave_allreduce_sum_u32(cnt[rb]);
+            const int hl = rbase / a.tauP;
+            if (lane == 0 && tot && hl < a.g)
+                atomicAdd(a.nnz + (size_t)bl * a.Hq + (size_t)hkv * a.g + hl, (unsigned long long)tot);
+        }
+    }
+}
+
+struct Plan { int tauP, RP, waves, rb, nsplit, keys_per_split; };
+
+Plan make_plan(const vlc_shape& s) {
+    Plan p;
+    const int g = s.Hq / s.Hkv;
+    p.tauP = (s.tau + 31) / 32 * 32;
+    p.RP = g * p.tauP;
+    if (p.RP <= 128) { p.waves = 4; p.rb = 1; }
+    else if (p.RP <= 256) { p.waves = 4; p.rb = 2; }
+    else { p.waves = 8; p.rb = 2; }
+    const int groups = s.B * s.L * s.Hkv;
+    const int chunks = (s.m + kChunk - 1) / kChunk;
+    int ns = (2048 + groups - 1) / groups;          // aim for a couple of thousand blocks
+    if (ns > chunks) ns = chunks;
+    if (ns < 1) ns = 1;
+    const int cps = (chunks + ns - 1) / ns;
+    p.keys_per_split = cps * kChunk;
+    p.nsplit = (s.m + p.keys_per_split - 1) / p.keys_per_split;
+    return p;
+}
+
+MfmaArgs make_args(const ScoreArgs& a, const Plan& p) {
+    MfmaArgs m;
+    const vlc_shape& s = a.s;
+    m.q_win = (const bf16_t*)a.q_win; m.k = (const bf16_t*)a.k; m.sm_scale = a.sm_scale;
+    m.part = (float2*)a.workspace;
+    m.row_max = a.row_max; m.row_sum = a.row_sum; m.row_max_t = nullptr;
+    m.scores = a.scores; m.nnz = (unsigned long long*)a.nnz;
+    m.log2p = log2f(a.p);
+    m.L = s.L; m.Hq = s.Hq; m.Hkv = s.Hkv; m.g = s.Hq / s.Hkv; m.m = s.m; m.tau = s.tau;
+    m.tauP = p.tauP; m.RP = p.RP; m.keys_per_split = p.keys_per_split; m.nsplit = p.nsplit;
+    return m;
+}
+
+size_t part_bytes(const vlc_shape& s, const Plan& p) {
+    return ((size_t)s.B * s.L * s.Hkv * p.nsplit * p.RP * sizeof(float2) + 255) / 256 * 256;
+}
+
+}  // namespace
+
+bool score_mfma_supported(const vlc_shape& s) {
+    if (s.dtype != VLC_BF16 || s.d != kD) return false;
+    const int g = s.Hq / s.Hkv;
+    return g * ((s.tau + 31) / 32 * 32) <= 512;
+}
+
+size_t score_mfma_workspace_bytes(const vlc_shape& s) {
+    if (!score_mfma_supported(s)) return 0;
+    return part_bytes(s, make_plan(s));
+}
+
+hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
+    const vlc_shape& s = a.s;
+    const Plan p = make_plan(s);
+    MfmaArgs m = make_args(a, p);
+    const int groups = s.B * s.L * s.Hkv;
+    dim3 grid(p.nsplit, groups);
+    if (p.waves == 4 && p.rb == 1) rowstats_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
+    else if (p.waves == 4) rowstats_mfma_kernel<4, 2><<<grid, 256, 0, a.stream>>>(m);
+    else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);
+    const size_t n = (size_t)groups * p.RP;
+    rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
+        m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv);
+    return hipGetLastError();
+}
+
+hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t) {
+    const vlc_shape& s = a.s;
+    const Plan p = make_plan(s);
+    MfmaArgs m = make_args(a, p);
+    if (have_row_max_t) m.row_max_t = a.row_max_t;
+    dim3 grid(p.nsplit, s.B * s.L * s.Hkv);
+    if (p.waves == 4 && p.rb == 1) colsweep_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
+    else if (p.waves == 4) colsweep_mfma_kernel<4, 2><<<grid, 256, 0, a.stream>>>(m);
+    else colsweep_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);
+    return hipGetLastError();
+}
+
+}  // namespace vlc
