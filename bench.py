@@ -73,7 +73,7 @@ def main() -> int:
         dq[t].copy_(torch.from_numpy(d["q"]).to(dt))
         dk[t].copy_(torch.from_numpy(d["k_new"]).to(dt))
         dv[t].copy_(torch.from_numpy(d["v_new"]).to(dt))
-    out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device=dev)
+    out = torch.empty((T, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device=dev)
     gen_s = time.time() - t0
 
     shape = V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
@@ -83,8 +83,7 @@ def main() -> int:
         if ev: ev[0].record()
         path.compress(q_win, k, v, sm)
         if ev: ev[1].record()
-        for t in range(T):
-            path.decode(0, cfg.L, dq[t], dk[t], dv[t], sm, out)
+        path.decode_steps(0, cfg.L, T, dq, dk, dv, sm, out)      # T launches enqueued from one C loop
         if ev: ev[2].record()
 
     for _ in range(args.warmup):
@@ -111,7 +110,7 @@ def main() -> int:
     e0.record()
     for t in range(T):
         for l in range(cfg.L):
-            path.decode(l, l + 1, dq[t, l], dk[t, l], dv[t, l], sm, out[l])
+            path.decode(l, l + 1, dq[t, l], dk[t, l], dv[t, l], sm, out[t, l])
     e1.record()
     torch.cuda.synchronize()
     per_layer_us = e0.elapsed_time(e1) * 1e3 / (T * cfg.L)

@@ -50,7 +50,7 @@ typedef void* vlc_stream;
 
 /* Problem shape, uniform over the batch (every request has the same m and tau).
  * Supported: d in {64, 128}; Hq % Hkv == 0 with g <= 8; 1 <= tau <= m; g * tau <= 512;
- * L <= 1024; dtype is the storage type of Q, K, V and of the decode output. */
+ * L <= 1024; B * L <= 2048; dtype is the storage type of Q, K, V and of the decode output. */
 typedef struct {
     int32_t B, L, Hq, Hkv, d, m, tau;
     int32_t dtype;             /* vlc_dtype */
@@ -189,6 +189,17 @@ vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t
 vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_end,
                            const void* q, const void* k_new, const void* v_new,
                            const float* sm_scale, void* out, vlc_stream stream);
+
+/*
+ * vlc_decode_attn_steps -- n_steps consecutive vlc_decode_attn calls (paper Sec. 2.1, one appended
+ * token per step) enqueued from one C loop, for callers whose per-call overhead would otherwise
+ * exceed the kernel time.  Step t uses slice t of every tensor:
+ * q, out [n_steps, layers in range, B, Hq, d];  k_new, v_new [n_steps, layers in range, B, Hkv, d].
+ * Same errors as vlc_decode_attn; steps enqueued before a failing one stay enqueued.
+ */
+vlc_status vlc_decode_attn_steps(vlc_cache* cache, int32_t layer_begin, int32_t layer_end, int32_t n_steps,
+                                 const void* q, const void* k_new, const void* v_new,
+                                 const float* sm_scale, void* out, vlc_stream stream);
 
 #ifdef __cplusplus
 }

@@ -69,6 +69,8 @@ def _load() -> C.CDLL:
     lib.vlc_topk_compact.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
     lib.vlc_decode_attn.restype = C.c_int
     lib.vlc_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.vlc_decode_attn_steps.restype = C.c_int
+    lib.vlc_decode_attn_steps.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     return lib
 
 
@@ -180,3 +182,8 @@ def vlc_topk_compact(cache: Cache, scores, k, n_recent, k_full, v_full, idx_out)
 def vlc_decode_attn(cache: Cache, layer_begin, layer_end, q, k_new, v_new, sm_scale, out) -> None:
     _check(lib.vlc_decode_attn(cache.handle, int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new),
                                _ptr(sm_scale), _ptr(out), _stream()))
+
+
+def vlc_decode_attn_steps(cache: Cache, layer_begin, layer_end, n_steps, q, k_new, v_new, sm_scale, out) -> None:
+    _check(lib.vlc_decode_attn_steps(cache.handle, int(layer_begin), int(layer_end), int(n_steps), _ptr(q),
+                                     _ptr(k_new), _ptr(v_new), _ptr(sm_scale), _ptr(out), _stream()))

@@ -43,6 +43,7 @@ vlc_status check_shape(const vlc_shape* s) {
     if ((int64_t)g * s->tau > 512) return fail(VLC_ERR_SHAPE, "g * tau = %d exceeds 512 window rows per KV head", g * s->tau);
     if (s->L > vlc::kMaxLayers) return fail(VLC_ERR_SHAPE, "L = %d exceeds %d", s->L, vlc::kMaxLayers);
     if ((int64_t)s->B * s->L * s->Hq > 65535) return fail(VLC_ERR_SHAPE, "B * L * Hq = %lld exceeds 65535", (long long)s->B * s->L * s->Hq);
+    if ((int64_t)s->B * s->L > 2048) return fail(VLC_ERR_SHAPE, "B * L = %lld exceeds 2048", (long long)s->B * s->L);
     if ((double)s->m * s->d * s->Hkv * s->L * s->B > 4.0e12) return fail(VLC_ERR_SHAPE, "K tensor larger than 4e12 elements");
     return VLC_OK;
 }
@@ -282,9 +283,7 @@ vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t
         return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: scores, k, k_full and v_full must not be NULL");
     if (n_recent < 0) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: n_recent = %d is negative", n_recent);
     hipStream_t hs = (hipStream_t)stream;
-    hipError_t e = vlc::launch_fill_u64((uint64_t*)cache->dev.status, 2, 0, hs);     // clear the sticky flag
-    if (e != hipSuccess) return hip_fail(e, "vlc_topk_compact clear status");
-    e = vlc::launch_topk_compact(*cache, scores, k, n_recent, k_full, v_full, idx_out, hs);
+    hipError_t e = vlc::launch_topk_compact(*cache, scores, k, n_recent, k_full, v_full, idx_out, hs);
     if (e != hipSuccess) return hip_fail(e, "vlc_topk_compact");
     cache->compacted = true;
     memset(cache->appended, 0, sizeof(cache->appended));
@@ -316,6 +315,28 @@ vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_
     if (e != hipSuccess) return hip_fail(e, "vlc_decode_attn");
     if (k_new)
         for (int l = layer_begin; l < layer_end; ++l) cache->appended[l] += 1;
+    return VLC_OK;
+}
+
+vlc_status vlc_decode_attn_steps(vlc_cache* cache, int32_t layer_begin, int32_t layer_end, int32_t n_steps,
+                                 const void* q, const void* k_new, const void* v_new, const float* sm_scale,
+                                 void* out, vlc_stream stream) {
+    if (!cache) return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn_steps: cache is NULL");
+    if (n_steps < 1) return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn_steps: n_steps = %d", n_steps);
+    if (!q || !k_new || !v_new || !out)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn_steps: q, k_new, v_new and out must not be NULL");
+    if (layer_begin < 0 || layer_end > cache->shape.L || layer_begin >= layer_end)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_decode_attn_steps: layer range [%d, %d) is outside [0, %d)", layer_begin, layer_end, cache->shape.L);
+    const vlc_shape& s = cache->shape;
+    const size_t es = elem_size(s.dtype);
+    const size_t nl = (size_t)(layer_end - layer_begin);
+    const size_t q_step = nl * s.B * s.Hq * s.d * es, kv_step = nl * s.B * s.Hkv * s.d * es;
+    for (int t = 0; t < n_steps; ++t) {
+        vlc_status st = vlc_decode_attn(cache, layer_begin, layer_end, (const char*)q + t * q_step,
+                                        (const char*)k_new + t * kv_step, (const char*)v_new + t * kv_step, sm_scale,
+                                        (char*)out + t * q_step, stream);
+        if (st != VLC_OK) return st;
+    }
     return VLC_OK;
 }
 

@@ -11,35 +11,44 @@
 namespace vlc {
 namespace {
 
-// One block for the whole batch (B*L is a few hundred entries): validates the budgets, lays the
-// slabs of each request out back to back, and builds the decode work list.
+// One block for the whole batch (B*L is a few hundred entries): clears the sticky status, validates
+// the budgets, lays the slabs of each request out back to back, and builds the decode work list.
+// Everything is staged in LDS so that the serial prefix sums never wait on global memory.
+constexpr int kLayoutMaxBL = 2048;     // B*L entries staged in LDS; larger batches take the global path
+
 __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, int B, int L, int Hkv, int m,
                                                      int d, int T_max, int64_t slots_per_request, int unit_slots,
                                                      int64_t max_items, CacheDev dev) {
-    __shared__ int bad[64];
+    __shared__ int32_t sKept[kLayoutMaxBL];
+    __shared__ int32_t sFirst[kLayoutMaxBL];        // first work item of (b, l), kv head 0
+    __shared__ int64_t sSlot[kLayoutMaxBL];
+    __shared__ int sBad;
     const int tid = threadIdx.x;
-    // budgets in range?
-    for (int x = tid; x < B * L; x += blockDim.x) {
+    const int BL = B * L;
+    if (tid < 4) dev.status[tid] = 0;
+    if (tid == 0) sBad = 0;
+    __syncthreads();
+    for (int x = tid; x < BL; x += blockDim.x) {
         int kk = k[x];
         if (kk < 1 || kk > m) {
             set_sticky(dev.status, VLC_ERR_INVALID_ARG, x / L, x % L, kk);
             kk = 0;
         }
-        dev.kept[x] = kk;
+        sKept[x] = kk;
     }
-    for (int x = tid; x < B * L * Hkv; x += blockDim.x) dev.counters[x] = 0;
+    for (int x = tid; x < BL * Hkv; x += blockDim.x) dev.counters[x] = 0;
     __syncthreads();
     // slab offsets, one thread per request; a request whose budgets do not fit keeps nothing
     for (int b = tid; b < B; b += blockDim.x) {
         int64_t acc = 0;
-        for (int l = 0; l < L; ++l) acc += dev.kept[b * L + l] + T_max;
+        for (int l = 0; l < L; ++l) acc += sKept[b * L + l] + T_max;
         const bool over = acc > slots_per_request;
         if (over) set_sticky(dev.status, VLC_ERR_CAPACITY, b, -1, (int)min(acc, (int64_t)INT32_MAX));
         acc = 0;
         for (int l = 0; l < L; ++l) {
-            if (over) dev.kept[b * L + l] = 0;
-            dev.slot_off[b * L + l] = (int64_t)b * slots_per_request + acc;
-            acc += dev.kept[b * L + l] + T_max;
+            if (over) sKept[b * L + l] = 0;
+            sSlot[b * L + l] = (int64_t)b * slots_per_request + acc;
+            acc += sKept[b * L + l] + T_max;
         }
     }
     __syncthreads();
@@ -49,34 +58,37 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         for (int l = 0; l < L; ++l) {
             dev.layer_item_start[l] = (int)acc;
             for (int b = 0; b < B; ++b) {
-                const int kk = dev.kept[b * L + l];
+                const int kk = sKept[b * L + l];
                 const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
-                for (int h = 0; h < Hkv; ++h) dev.row_item_first[(size_t)(b * L + l) * Hkv + h] = (int)(acc + (int64_t)h * nu);
+                sFirst[b * L + l] = (int)acc;
                 acc += (int64_t)nu * Hkv;
             }
         }
         dev.layer_item_start[L] = (int)acc;
-        bad[0] = acc > max_items;       // cannot happen for budgets that passed the capacity check
-    }
-    __syncthreads();
-    if (bad[0]) {
-        if (tid == 0) {
+        if (acc > max_items) {          // cannot happen for budgets that passed the capacity check
             set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
             for (int l = 0; l <= L; ++l) dev.layer_item_start[l] = 0;
+            sBad = 1;
         }
-        return;
     }
-    for (int x = tid; x < B * L * Hkv; x += blockDim.x) {
+    __syncthreads();
+    for (int x = tid; x < BL; x += blockDim.x) {
+        dev.kept[x] = sKept[x];
+        dev.slot_off[x] = sSlot[x];
+    }
+    if (sBad) return;
+    for (int x = tid; x < BL * Hkv; x += blockDim.x) {
         const int h = x % Hkv, bl = x / Hkv, b = bl / L, l = bl % L;
-        const int kk = dev.kept[bl];
+        const int kk = sKept[bl];
         const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
         const int cap = kk + T_max;
-        const int64_t so = dev.slot_off[bl];
+        const int64_t so = sSlot[bl];
         WorkItem it;
         it.row_abs = x; it.kept = kk; it.b = b; it.l = l; it.pad[0] = it.pad[1] = 0;
         it.kbase = ((so * 2 * Hkv) + (int64_t)h * cap) * d;
         it.idx_base = so * Hkv + (int64_t)h * cap;
-        const int w0 = dev.row_item_first[x];
+        const int w0 = sFirst[bl] + h * nu;
+        dev.row_item_first[x] = w0;
         for (int u = 0; u < nu; ++u) {
             it.unit = u;
             it.key0 = u * unit_slots;

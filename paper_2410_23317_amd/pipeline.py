@@ -64,6 +64,9 @@ class VLCachePath:
     def decode(self, layer_begin, layer_end, q, k_new, v_new, sm_scale, out) -> None:
         V.vlc_decode_attn(self.cache, layer_begin, layer_end, q, k_new, v_new, sm_scale, out)
 
+    def decode_steps(self, layer_begin, layer_end, n_steps, q, k_new, v_new, sm_scale, out) -> None:
+        V.vlc_decode_attn_steps(self.cache, layer_begin, layer_end, n_steps, q, k_new, v_new, sm_scale, out)
+
     def status(self) -> None:
         V.vlc_cache_status(self.cache)
 

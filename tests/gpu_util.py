@@ -3,6 +3,7 @@ binding, compare with the oracle under the stated tolerances."""
 from __future__ import annotations
 
 import numpy as np
+import pytest
 import torch
 
 import workloads as W
@@ -18,7 +19,7 @@ def make_shape(cfg):
     return V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
 
 
-def upload(cfg, want_v=True, workers=8):
+def upload(cfg, want_v=True, workers=16):
     """q_win [B,L,Hq,tau,d], k, v [B,L,Hkv,m,d] in the storage dtype on the GPU, sm_scale [L] fp32."""
     dt = torch_dtype(cfg)
     dev = torch.device("cuda")
@@ -84,3 +85,110 @@ def check_nnz(nnz_gpu, q_win, k, scale, p, what, rel=1e-5):
     d = np.abs(nnz_gpu - nnz_o)
     assert np.all(d <= border), f"{what}: counts differ by {d.tolist()} with only {border.tolist()} borderline entries"
     return nnz_o, int(d.sum())
+
+
+SCORE_TOL = dict(atol=1e-7, rtol=5e-5)
+
+
+def out_tol(cfg):
+    return dict(atol=2e-2, rtol=1e-2) if cfg.dtype == "bf16" else dict(atol=1e-4, rtol=1e-4)
+
+
+def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, requests_to_check=None, per_layer_decode=False,
+                  dev=None):
+    """Whole path on the GPU; oracle on every (or the listed) request/layer."""
+    import paper_2410_23317_amd as V
+    from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
+
+    print(f"[case] cfg={cfg.name} cid={cfg.cid} m={cfg.m} tau={cfg.tau} d={cfg.d} g={cfg.g} alpha={alpha} "
+          f"steps={n_steps} n_recent={n_recent}", flush=True)
+    shape = make_shape(cfg)
+    if dev is None:
+        dev = upload(cfg)
+    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=max(n_steps, 1), n_recent=n_recent, want_idx=True)
+    path.compress(dev["q_win"], dev["k"], dev["v"], dev["sm_scale"])
+    path.status()
+    torch.cuda.synchronize()
+    scales = W.sm_scale(cfg)
+    full = layers_to_check is None and requests_to_check is None
+    reqs = range(cfg.B) if requests_to_check is None else requests_to_check
+    lays = range(cfg.L) if layers_to_check is None else layers_to_check
+
+    scores = path.scores.cpu().numpy()
+    nnz = path.nnz.cpu().numpy()
+    kk = path.k.cpu().numpy()
+    # properties that hold at any size
+    np.testing.assert_allclose(scores.sum(-1), cfg.g * cfg.tau, rtol=1e-4)
+    lo = O.k_min(cfg.m)
+    assert np.all(kk >= lo) and np.all(kk <= cfg.m)
+    b_tot = W.budget_total(cfg, alpha)
+    for b in range(cfg.B):
+        k_o, beta_o = O.allocate(nnz[b], cfg.m, alpha[0], alpha[1])
+        assert np.array_equal(kk[b], k_o), f"budgets of request {b} differ from Alg. 1 on the GPU's own counts"
+        np.testing.assert_allclose(path.beta[b].cpu().numpy(), beta_o, rtol=1e-6)
+        quota_ok = (nnz[b].sum(1) * b_tot / nnz[b].sum() >= lo).all()
+        if quota_ok:
+            assert int(kk[b].sum()) == b_tot
+
+    caches = {}
+    flips = swaps = 0
+    for b in reqs:
+        nnz_oracle = []
+        for l in lays:
+            t = W.layer_inputs(cfg, b, l)
+            psi, _, M, Z = O.score(t["q_win"], t["k"], scales[l])
+            what = f"{cfg.name} b={b} l={l}"
+            assert_close(scores[b, l], psi, what=what + " scores", **SCORE_TOL)
+            assert_close(path.row_max[b, l].cpu().numpy(), M, atol=2e-5, rtol=2e-6, what=what + " row_max")
+            assert_close(path.row_sum[b, l].cpu().numpy(), Z, atol=0, rtol=5e-5, what=what + " row_sum")
+            n_o, d = check_nnz(nnz[b, l], t["q_win"], t["k"], scales[l], 0.01, what + " nnz")
+            flips += d
+            nnz_oracle.append(n_o)
+            np.testing.assert_allclose(path.gamma[b, l].cpu().numpy(), 1 - nnz[b, l] / O.region_size(cfg.m, cfg.tau),
+                                       rtol=1e-6, atol=1e-7)
+            kc, vc, idx = cache_layer_view(path.cache, b, l)
+            kc, vc, idx = kc.float().cpu().numpy(), vc.float().cpu().numpy(), idx.cpu().numpy()
+            for h in range(cfg.Hkv):
+                swaps += check_topk(idx[h], psi[h], int(kk[b, l]), what + f" hkv={h} topk", n_recent=n_recent)
+                assert np.array_equal(path.idx_out[b, l, h, : kk[b, l]].cpu().numpy(), idx[h])
+                assert np.array_equal(kc[h], t["k"][h][idx[h]]), what + " gathered K rows"
+                assert np.array_equal(vc[h], t["v"][h][idx[h]]), what + " gathered V rows"
+            caches[(b, l)] = ([kc[h] for h in range(cfg.Hkv)], [vc[h] for h in range(cfg.Hkv)])
+        if full:
+            k_e2e, _ = O.allocate(np.stack(nnz_oracle), cfg.m, alpha[0], alpha[1])
+            if not np.array_equal(k_e2e, kk[b]):
+                assert flips > 0, "budgets differ from the oracle's although every count matches"
+                pytest.fail(f"request {b}: budgets differ from the oracle's end to end because of {flips} "
+                            f"borderline threshold decisions: {kk[b].tolist()} vs {k_e2e.tolist()}")
+    print(f"[compress ok] borderline count flips={flips} topk swaps={swaps}", flush=True)
+
+    # decode steps: the GPU appends into its cache, the oracle into its own lists
+    dt = torch_dtype(cfg)
+    out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device="cuda")
+    for step in range(n_steps):
+        d_dev, d_host = decode_upload(cfg, step)
+        if per_layer_decode:
+            for l in range(cfg.L):
+                path.decode(l, l + 1, d_dev["q"][l], d_dev["k_new"][l], d_dev["v_new"][l], dev["sm_scale"], out[l])
+        else:
+            path.decode(0, cfg.L, d_dev["q"], d_dev["k_new"], d_dev["v_new"], dev["sm_scale"], out)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy()
+        for (b, l), (kc, vc) in caches.items():
+            for h in range(cfg.Hkv):
+                kc[h] = np.concatenate([kc[h], d_host["k_new"][l, b, h][None]], 0)
+                vc[h] = np.concatenate([vc[h], d_host["v_new"][l, b, h][None]], 0)
+            want = O.decode_attn(d_host["q"][l, b], kc, vc, scales[l])
+            assert_close(got[l, b], want, what=f"{cfg.name} decode step {step} b={b} l={l}", **out_tol(cfg))
+    path.status()
+    # the cache now holds the appended rows too
+    if n_steps:
+        (b, l), (kc, vc) = next(iter(caches.items()))
+        gk, gv, gi = cache_layer_view(path.cache, b, l, appended=n_steps)
+        assert np.array_equal(gk.float().cpu().numpy()[0], kc[0])
+        assert np.array_equal(gv.float().cpu().numpy()[0], vc[0])
+        assert gi[0, -1].item() == cfg.m + n_steps - 1
+    print("[decode ok]", flush=True)
+    return path
+
+

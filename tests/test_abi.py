@@ -1,0 +1,98 @@
+"""The C-ABI boundary without a GPU: every function include/vlcache.h declares is exported by the
+built library, and host-side validation rejects bad calls before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def V():
+    lib = os.path.join(ROOT, "paper_2410_23317_amd", "libvlcache.so")
+    if not os.path.exists(lib):
+        import __graft_entry__
+        __graft_entry__.build()
+    import paper_2410_23317_amd as V
+    return V
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "vlcache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vlc_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_five_calls():
+    names = declared_functions()
+    for n in ("vlc_score", "vlc_sparsity", "vlc_allocate", "vlc_topk_compact", "vlc_decode_attn",
+              "vlc_cache_create", "vlc_cache_destroy", "vlc_workspace_bytes", "vlc_cache_bytes"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(V):
+    for n in declared_functions():
+        assert hasattr(V.lib, n), f"{n} is declared in include/vlcache.h but not exported"
+    assert "gfx950" in V.vlc_version()
+
+
+def test_shape_validation(V):
+    ok = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
+    assert V.vlc_workspace_bytes(ok) > 0
+    bad = [
+        (dict(Hq=4, Hkv=3), V.VLC_ERR_SHAPE), (dict(d=96), V.VLC_ERR_SHAPE), (dict(Hq=18, Hkv=2), V.VLC_ERR_SHAPE),
+        (dict(tau=600, m=512), V.VLC_ERR_SHAPE), (dict(tau=0), V.VLC_ERR_SHAPE), (dict(L=0), V.VLC_ERR_SHAPE),
+        (dict(Hq=8, Hkv=1, tau=128), V.VLC_ERR_SHAPE), (dict(dtype=7), V.VLC_ERR_DTYPE),
+    ]
+    base = dict(B=1, L=2, Hq=4, Hkv=2, d=64, m=512, tau=32, dtype=V.VLC_F32)
+    for kw, code in bad:
+        s = V.make_shape(**{**base, **kw})
+        assert V.lib.vlc_workspace_bytes(C.byref(s)) == 0
+        st = V.lib.vlc_score(C.byref(s), 1, 1, None, 0.01, 1, 1, 1, None, 1, 1 << 30, None)
+        assert st == code, (kw, st, V.vlc_last_error_string())
+        assert V.vlc_last_error_string()
+
+
+def test_argument_validation_happens_before_any_launch(V):
+    s = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
+    sp = C.byref(s)
+    assert V.lib.vlc_score(sp, None, 1, None, 0.01, 1, 1, 1, None, 1, 1 << 30, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_score(sp, 1, 1, None, 0.01, 1, 1, 1, None, 1, 16, None) == V.VLC_ERR_CAPACITY
+    assert V.lib.vlc_score(sp, 1, 1, None, 1.5, 1, 1, 1, 1, 1, 1 << 30, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_sparsity(sp, None, None, None, None, 0.01, None, None, None, 0, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_allocate(sp, 1, 0, 10, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_allocate(sp, 1, 11, 10, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_allocate(sp, None, 1, 10, 1, None, None) == V.VLC_ERR_INVALID_ARG
+
+
+def test_cache_bookkeeping_errors(V):
+    s = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
+    n = V.vlc_cache_bytes(s, 8, 120)
+    assert n > 2 * 4 * 2 * 64 * (120 + 16)           # at least the K and V slabs
+    assert V.vlc_cache_bytes(s, 16, 120) > n
+    h = C.c_void_p()
+    assert V.lib.vlc_cache_create(C.byref(s), 8, 120, 4096, n - 1, C.byref(h)) == V.VLC_ERR_CAPACITY
+    assert V.lib.vlc_cache_create(C.byref(s), 8, 120, 4096 + 8, n, C.byref(h)) == V.VLC_ERR_INVALID_ARG   # misaligned
+    assert V.lib.vlc_cache_create(C.byref(s), 8, 1, 4096, n, C.byref(h)) == V.VLC_ERR_INVALID_ARG         # sum_k_max < L
+    assert V.lib.vlc_cache_create(C.byref(s), 8, 120, 4096, n, C.byref(h)) == V.VLC_OK                    # no device access yet
+    lay = V.vlc_cache_layout()
+    assert V.lib.vlc_cache_get_layout(h, C.byref(lay)) == V.VLC_OK
+    assert lay.total_bytes == n and lay.slots_per_request == 120 + 2 * 8 and lay.kv_off % 256 == 0
+    # decode before compaction, bad layer ranges
+    assert V.lib.vlc_decode_attn(h, 0, 2, 1, None, None, None, 1, None) == V.VLC_ERR_INVALID_ARG
+    assert "vlc_topk_compact" in V.vlc_last_error_string()
+    assert V.lib.vlc_decode_attn(None, 0, 1, 1, None, None, None, 1, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_topk_compact(h, None, 1, 0, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_topk_compact(h, 1, 1, -1, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    V.lib.vlc_cache_destroy(h)
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2410_23317_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("miracle", ""), f"{f} mentions the oracle"
