@@ -32,6 +32,9 @@ def main() -> int:
     ap.add_argument("--decode-steps", type=int, default=-1)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (a known-size reference for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -75,6 +78,13 @@ def main() -> int:
         dv[t].copy_(torch.from_numpy(d["v_new"]).to(dt))
     out = torch.empty((T, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device=dev)
     gen_s = time.time() - t0
+
+    if args.calibrate_copy_mib > 0:
+        src = torch.full((args.calibrate_copy_mib << 20,), 1, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     shape = V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
     path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=T)

@@ -186,9 +186,9 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     const size_t es = elem_size(s->dtype);
     const size_t BL = (size_t)s->B * s->L;
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
-    // decode block-unit: 512 slots unless the mean row is short (measured: per-unit overhead, not
-    // balance, dominates on MI355X once a launch has a few hundred units)
-    plan->unit_slots = (sum_k_max / s->L + T_max / 2 >= 192) ? 512 : 256;
+    // decode block-unit: 256 slots, 512 once the mean row is long (measured on the ragged budgets of
+    // the 7B shapes: per-unit overhead against balance)
+    plan->unit_slots = (sum_k_max / s->L + T_max / 2 >= 768) ? 512 : 256;
     if (const char* e = getenv("VLC_UNIT_SLOTS")) {           // tuning knob
         const int v = atoi(e);
         if (v == 128 || v == 256 || v == 512) plan->unit_slots = v;
