@@ -42,6 +42,7 @@ struct DecodeParams {
     int layer_begin, n_layers, T_max;
     int appended;            // appends before this call
     int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
+    int prefetch;            // next tile's loads issued early (more registers, 2 blocks per CU)
     float default_scale;
 };
 
@@ -144,8 +145,8 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 template <typename T> struct IsBf16 { static constexpr bool value = false; };
 template <> struct IsBf16<bf16_t> { static constexpr bool value = true; };
 
-template <typename T, int D, int G, int NT>
-__global__ __launch_bounds__(256, (G <= 4 && NT == 1 ? 3 : 2)) void decode_kernel(DecodeParams P) {
+template <typename T, int D, int G, int NT, bool PF>
+__global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void decode_kernel(DecodeParams P) {
     constexpr bool BF = IsBf16<T>::value;
     constexpr int EP = Elem<T>::kPer16B;        // elements in a 16-byte chunk
     constexpr int LPR = D / EP;                 // lanes per K/V row
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(256, (G <= 4 && NT == 1 ? 3 : 2)) void decode_kerne
                     if (c < G) sL[wave][i * KPI + sub][c] = live ? mine * scale2 : -INFINITY;
                 }
             }
-            if (more) issue_k(t0 + TK);
+            if (more) issue_k(t0 + 4 * TK);
             __builtin_amdgcn_wave_barrier();
             // ---- softmax bookkeeping: 16-lane row r handles heads r*HR.., lane column j slots j, j+16
             float corr_row[HR];
@@ -347,16 +348,18 @@ __global__ __launch_bounds__(256, (G <= 4 && NT == 1 ? 3 : 2)) void decode_kerne
                     }
                 }
             }
-            if (more) issue_v(t0 + TK);
+            if (more) issue_v(t0 + 4 * TK);
             __builtin_amdgcn_wave_barrier();
         };
-        const int tw0 = key0 + wave * NT * TK;  // first slot of this wave
+        // tiles of the unit are dealt round-robin to the 4 waves, so a partly filled unit keeps all of them busy
+        const int tw0 = key0 + wave * TK;
         if (tw0 < len) { issue_k(tw0); issue_v(tw0); }
 #pragma unroll 1
         for (int t = 0; t < NT; ++t) {
-            const int t0 = tw0 + t * TK;
+            const int t0 = tw0 + t * 4 * TK;
             if (t0 >= len) break;               // wave-uniform
-            const bool more = (t + 1 < NT) && (t0 + TK < len);
+            const bool more = PF && (t + 1 < NT) && (t0 + 4 * TK < len);
+            if (!PF && t > 0) { issue_k(t0); issue_v(t0); }
             const bool full = (t0 + TK <= len);
             if (full) tile_body(std::true_type{}, t0, more); else tile_body(std::false_type{}, t0, more);
         }
@@ -454,7 +457,9 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
 
 template <typename T, int D, int G, int NT>
 hipError_t launch_nt(const DecodeParams& P, int grid, int rows, hipStream_t st) {
-    decode_kernel<T, D, G, NT><<<grid, 256, 0, st>>>(P);
+
+    if (P.prefetch && NT > 1) decode_kernel<T, D, G, NT, true><<<grid, 256, 0, st>>>(P);
+    else decode_kernel<T, D, G, NT, false><<<grid, 256, 0, st>>>(P);
     if (P.merge_mode == 2) decode_merge_kernel<T, D, G, NT><<<rows, 256, 0, st>>>(P);
     return hipGetLastError();
 }
@@ -498,7 +503,8 @@ hipError_t launch_decode(const DecodeArgs& a) {
     P.layer_begin = a.layer_begin; P.n_layers = a.n_layers; P.T_max = c.T_max;
     P.appended = a.appended;
     P.default_scale = 1.0f / sqrtf((float)s.d);
-    P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knob
+    P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knobs
+    P.prefetch = env_int("VLC_DECODE_PREFETCH", 0);
     const int rows = a.n_layers * s.B * s.Hkv;
     // Upper bound on the block-units of the layer range: every row at the full prompt length, and
     // never more than the whole work list.
