@@ -200,7 +200,7 @@ __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, floa
 // ------------------------------------------------------------------------------------------------
 // Sweep 2: column sums of the softmax over all window rows of the KV group, and per-head counts.
 template <int WAVES, int RB>
-__global__ __launch_bounds__(WAVES * 64) void colsweep_mfma_kernel(MfmaArgs a) {
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_kernel(MfmaArgs a) {   // waves per SIMD: 2 blocks of 8 waves, or 3 of 4
     constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) bf16_t sK[kChunk * kPitch];
     __shared__ float sCol[WAVES][kChunk];
@@ -262,14 +262,14 @@ __global__ __launch_bounds__(WAVES * 64) void colsweep_mfma_kernel(MfmaArgs a) {
                         const float ea = fmaf(acc[i], c, -mc[rb][i]);
                         const float e = valid ? exp2_fast(ea) : 0.f;
                         col = fmaf(e, iz[rb][i], col);
-                        cnt[rb] += (valid && ea >= a.log2p) ? 1u : 0u;
+                        cnt[rb] += (uint32_t)__popcll(__ballot(valid && ea >= a.log2p));   // wave-wide count on the scalar unit
                     }
                 } else {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const float ea = fmaf(acc[i], c, -mc[rb][i]);
                         col = fmaf(exp2_fast(ea), iz[rb][i], col);
-                        cnt[rb] += (ea >= a.log2p) ? 1u : 0u;
+                        cnt[rb] += (uint32_t)__popcll(__ballot(ea >= a.log2p));
                     }
                 }
             }
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(WAVES * 64) void colsweep_mfma_kernel(MfmaArgs a) {
         for (int rb = 0; rb < RB; ++rb) {
             const int rbase = (wave * RB + rb) * 32;
             if (rbase >= a.RP) continue;
-            const uint32_t tot = wave_allreduce_sum_u32(cnt[rb]);
+            const uint32_t tot = cnt[rb];                        // already a wave-wide count
             const int hl = rbase / a.tauP;
             if (lane == 0 && tot && hl < a.g)
                 atomicAdd(a.nnz + (size_t)bl * a.Hq + (size_t)hkv * a.g + hl, (unsigned long long)tot);
@@ -305,8 +305,8 @@ Plan make_plan(const vlc_shape& s) {
     p.tauP = (s.tau + 31) / 32 * 32;
     p.RP = g * p.tauP;
     if (p.RP <= 128) { p.waves = 4; p.rb = 1; }
-    else if (p.RP <= 256) { p.waves = 4; p.rb = 2; }
-    else { p.waves = 8; p.rb = 2; }
+    else if (p.RP <= 256) { p.waves = 8; p.rb = 1; }      // one row block per wave keeps the sweeps at 8 waves per CU
+    else { p.waves = 16; p.rb = 1; }
     const int groups = s.B * s.L * s.Hkv;
     const int chunks = (s.m + kChunk - 1) / kChunk;
     int ns = (2048 + groups - 1) / groups;          // aim for a couple of thousand blocks
@@ -354,9 +354,9 @@ hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
     MfmaArgs m = make_args(a, p);
     const int groups = s.B * s.L * s.Hkv;
     dim3 grid(p.nsplit, groups);
-    if (p.waves == 4 && p.rb == 1) rowstats_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
-    else if (p.waves == 4) rowstats_mfma_kernel<4, 2><<<grid, 256, 0, a.stream>>>(m);
-    else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);
+    if (p.waves == 4) rowstats_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
+    else if (p.waves == 8) rowstats_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
+    else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);        // measured faster than 16 x 1 for this sweep
     const size_t n = (size_t)groups * p.RP;
     rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
         m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv);
@@ -369,9 +369,9 @@ hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t) {
     MfmaArgs m = make_args(a, p);
     if (have_row_max_t) m.row_max_t = a.row_max_t;
     dim3 grid(p.nsplit, s.B * s.L * s.Hkv);
-    if (p.waves == 4 && p.rb == 1) colsweep_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
-    else if (p.waves == 4) colsweep_mfma_kernel<4, 2><<<grid, 256, 0, a.stream>>>(m);
-    else colsweep_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);
+    if (p.waves == 4) colsweep_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
+    else if (p.waves == 8) colsweep_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
+    else colsweep_mfma_kernel<16, 1><<<grid, 1024, 0, a.stream>>>(m);
     return hipGetLastError();
 }
 
