@@ -107,11 +107,7 @@ vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k, c
     const bool mfma = ws_plan(*shape).mfma;
     hipError_t e = run_rowstats(a, mfma);
     if (e != hipSuccess) return hip_fail(e, "vlc_score row statistics");
-    if (nnz) {
-        e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, a.stream);
-        if (e != hipSuccess) return hip_fail(e, "vlc_score clear counts");
-    }
-    e = run_colsweep(a, mfma, true);
+    e = run_colsweep(a, mfma, true);              // the counters were zeroed by the row-statistics merge
     if (e != hipSuccess) return hip_fail(e, "vlc_score column sweep");
     return VLC_OK;
 }
@@ -139,9 +135,10 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
             hipError_t e = run_rowstats(a, wp.mfma);
             if (e != hipSuccess) return hip_fail(e, "vlc_sparsity row statistics");
             a.row_sum = nullptr;
-            have_t = true;
+            have_t = true;                          // that pass also zeroed the counters
         }
-        hipError_t e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, hs);
+        hipError_t e = hipSuccess;
+        if (!have_t) e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, hs);
         if (e != hipSuccess) return hip_fail(e, "vlc_sparsity clear counts");
         e = run_colsweep(a, wp.mfma, have_t);
         if (e != hipSuccess) return hip_fail(e, "vlc_sparsity count sweep");

@@ -171,15 +171,18 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
     const int sub = lane / LPR, c = lane % LPR;
     const int srow = lane >> 4, scol = lane & 15;
     const bool appending = P.k_new != nullptr;
-    const int w_begin = P.dev.layer_item_start[P.layer_begin];
-    const int w_end = P.dev.layer_item_start[P.layer_begin + P.n_layers];
-
     // One block-unit per block; the hardware dispatcher balances the ragged units.  The grid is a
-    // host-side upper bound on the units of the layer range, surplus blocks leave here.
-    const int w = w_begin + blockIdx.x;
-    if (w >= w_end) return;
+    // host-side upper bound on the units of the layer range, surplus blocks leave below.  A range
+    // that starts at layer 0 starts at unit 0, so the unit record does not wait for the range lookup
+    // (the grid never exceeds the list's capacity, so a surplus block reads an unused record).
+    int w = blockIdx.x;
+    if (P.layer_begin != 0) {
+        w += P.dev.layer_item_start[P.layer_begin];
+        if (w >= P.dev.layer_item_start[P.layer_begin + P.n_layers]) return;
+    }
     {
         const WorkItem itv = P.dev.items[w];
+        if (P.layer_begin == 0 && w >= P.dev.layer_item_start[P.n_layers]) return;
         const int kept = uniform(itv.kept), key0 = uniform(itv.key0), row_abs = uniform(itv.row_abs);
         const int unit = uniform(itv.unit), ib = uniform(itv.b), il = uniform(itv.l);
         const int64_t kbase = uniform64(itv.kbase), idx_base = uniform64(itv.idx_base);

@@ -75,11 +75,11 @@ struct ScoreArgs {
     hipStream_t stream;
 };
 size_t score_simple_workspace_bytes(const vlc_shape& s);
-hipError_t launch_rowstats_simple(const ScoreArgs& a);     // fills row_max, row_sum
+hipError_t launch_rowstats_simple(const ScoreArgs& a);     // fills row_max, row_sum; zeroes nnz if given
 hipError_t launch_colsweep_simple(const ScoreArgs& a);     // scores and/or nnz from row_max,row_sum
 bool score_mfma_supported(const vlc_shape& s);            // bf16, d = 128, g * roundup(tau, 32) <= 512
 size_t score_mfma_workspace_bytes(const vlc_shape& s);
-hipError_t launch_rowstats_mfma(const ScoreArgs& a);       // fills row_max, row_sum, row_max_t
+hipError_t launch_rowstats_mfma(const ScoreArgs& a);       // fills row_max, row_sum, row_max_t; zeroes nnz if given
 hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t);
 hipError_t launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t st);
 hipError_t launch_gamma(const vlc_shape& s, const uint64_t* nnz, float* gamma, hipStream_t st);

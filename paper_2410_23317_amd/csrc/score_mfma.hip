@@ -175,10 +175,13 @@ __global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
 
 // Merge the per-split partials: one thread per (group, padded row).  Writes the natural-log row
 // max and the row sum in the caller's [B,L,Hq,tau] layout and the exponent-domain max for sweep 2.
+// The first n_clear threads also zero the per-head counters that sweep 2 adds into.
 __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
                                            float* __restrict__ row_sum, float* __restrict__ row_max_t,
-                                           int groups, int nsplit, int RP, int tauP, int tau, int g, int Hq, int Hkv) {
+                                           int groups, int nsplit, int RP, int tauP, int tau, int g, int Hq, int Hkv,
+                                           uint64_t* __restrict__ nnz_clear, size_t n_clear) {
     const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x < n_clear) nnz_clear[x] = 0;
     if (x >= (size_t)groups * RP) return;
     const int r = (int)(x % RP), group = (int)(x / RP);
     const int hl = r / tauP, iw = r % tauP;
@@ -359,7 +362,8 @@ hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
     else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);        // measured faster than 16 x 1 for this sweep
     const size_t n = (size_t)groups * p.RP;
     rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
-        m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv);
+        m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv,
+        a.nnz, a.nnz ? (size_t)s.B * s.L * s.Hq : 0);
     return hipGetLastError();
 }
 

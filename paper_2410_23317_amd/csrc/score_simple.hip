@@ -93,10 +93,13 @@ __global__ __launch_bounds__(256) void rowstats_simple_kernel(
     }
 }
 
-// Merge the per-chunk partials of a window row: thread per (head row r, window row i).
+// Merge the per-chunk partials of a window row: thread per (head row r, window row i).  The first
+// n_clear threads also zero the per-head counters that the second sweep adds into.
 __global__ void rowstats_merge_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
-                                      float* __restrict__ row_sum, size_t rows, int nchunks) {
+                                      float* __restrict__ row_sum, size_t rows, int nchunks,
+                                      uint64_t* __restrict__ nnz_clear, size_t n_clear) {
     const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (x < n_clear) nnz_clear[x] = 0;
     if (x >= rows) return;
     const float2* p = part + x * nchunks;
     float M = -INFINITY;
@@ -180,7 +183,8 @@ hipError_t rowstats_impl(const ScoreArgs& a) {
     rowstats_simple_kernel<T, D><<<grid, 256, 0, a.stream>>>(
         (const T*)a.q_win, (const T*)a.k, a.sm_scale, (float2*)a.workspace, s.L, s.Hq, s.Hkv, s.m, s.tau, nchunks);
     rowstats_merge_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, a.stream>>>(
-        (const float2*)a.workspace, a.row_max, a.row_sum, rows, nchunks);
+        (const float2*)a.workspace, a.row_max, a.row_sum, rows, nchunks, a.nnz,
+        a.nnz ? (size_t)s.B * s.L * s.Hq : 0);
     return hipGetLastError();
 }
 

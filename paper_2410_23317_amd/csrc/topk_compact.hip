@@ -4,7 +4,7 @@
 //   layout : validates k[b][l], prefix-sums the slab offsets of a request's layers
 //   select : radix-select of the k-th largest score, then an ordered compaction that emits the
 //            kept positions ascending (ties to the lower position)
-//   gather : streams the kept 16-byte row chunks of K and V into the slabs
+//   gather : one block per work-list unit streams the kept rows of K and V into the slabs
 #include "common.h"
 #include "internal.h"
 
@@ -22,6 +22,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
     __shared__ int32_t sKept[kLayoutMaxBL];
     __shared__ int32_t sFirst[kLayoutMaxBL];        // first work item of (b, l), kv head 0
     __shared__ int64_t sSlot[kLayoutMaxBL];
+    __shared__ int64_t sScan[256];
     __shared__ int sBad;
     const int tid = threadIdx.x;
     const int BL = B * L;
@@ -52,23 +53,42 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         }
     }
     __syncthreads();
-    // work list: units per row, prefix over (layer, request)
-    if (tid == 0) {
-        int64_t acc = 0;
-        for (int l = 0; l < L; ++l) {
-            dev.layer_item_start[l] = (int)acc;
-            for (int b = 0; b < B; ++b) {
-                const int kk = sKept[b * L + l];
-                const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
-                sFirst[b * L + l] = (int)acc;
-                acc += (int64_t)nu * Hkv;
-            }
+    // work list: units per row, exclusive prefix over (layer, request) in that order.  Each thread
+    // sums a run of consecutive entries, the run totals are scanned across the block, then every
+    // thread walks its run again from its offset.
+    {
+        const int per = (BL + 255) / 256;
+        const int y0 = tid * per, y1 = min(BL, y0 + per);
+        int64_t run = 0;
+        for (int y = y0; y < y1; ++y) {
+            const int kk = sKept[(y % B) * L + y / B];
+            run += (int64_t)(kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1) * Hkv;
         }
-        dev.layer_item_start[L] = (int)acc;
-        if (acc > max_items) {          // cannot happen for budgets that passed the capacity check
-            set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
-            for (int l = 0; l <= L; ++l) dev.layer_item_start[l] = 0;
-            sBad = 1;
+        sScan[tid] = run;
+        __syncthreads();
+        for (int o = 1; o < 256; o <<= 1) {
+            const int64_t v = tid >= o ? sScan[tid - o] : 0;
+            __syncthreads();
+            sScan[tid] += v;
+            __syncthreads();
+        }
+        const int64_t total = sScan[255];
+        if (total > max_items) {            // cannot happen for budgets that passed the capacity check
+            if (tid == 0) {
+                set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
+                sBad = 1;
+            }
+            for (int l = tid; l <= L; l += 256) dev.layer_item_start[l] = 0;
+        } else {
+            int64_t acc = sScan[tid] - run;
+            for (int y = y0; y < y1; ++y) {
+                const int l = y / B, b = y % B;
+                const int kk = sKept[b * L + l];
+                if (b == 0) dev.layer_item_start[l] = (int)acc;
+                sFirst[b * L + l] = (int)acc;
+                acc += (int64_t)(kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1) * Hkv;
+            }
+            if (tid == 0) dev.layer_item_start[L] = (int)total;
         }
     }
     __syncthreads();
@@ -209,43 +229,39 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     }
 }
 
+// One block per unit of the decode work list: up to `unit_slots` kept rows of one (request, layer,
+// KV head) row.  The grid is the list's capacity, so it follows the budgets that fit the arena rather
+// than rows * m, and surplus blocks leave after two loads.  Each lane moves 16 bytes of one K row and
+// one V row per pass; the position of the next row is fetched before the stores are issued.  More
+// rows in flight per lane measured slower on every shape (the gathered reads are 256-byte pieces at
+// random DRAM pages; eight blocks per CU already keep enough of them outstanding).
 template <int ROWBYTES>
 __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_full, const char* __restrict__ v_full,
-                                                     CacheDev dev, int Hkv, int m, int T_max) {
+                                                     CacheDev dev, int L, int Hkv, int m, int T_max, int unit_slots,
+                                                     int elem_bytes) {
     constexpr int LPR = ROWBYTES / 16;          // lanes per row
-    constexpr int RPB = 256 / LPR;              // rows per block step
-    constexpr int U = 4;
-    const int row = blockIdx.y;
-    const int hkv = row % Hkv, bl = row / Hkv;
-    const int kk = dev.kept[bl];
-    if (kk == 0) return;
+    constexpr int RPB = 256 / LPR;              // rows per block pass
+    const int w = blockIdx.x;
+    const WorkItem it = dev.items[w];           // the grid never exceeds the list's capacity
+    if (w >= dev.layer_item_start[L]) return;
+    const int kk = it.kept, key0 = it.key0;
+    if (kk == 0 || key0 >= kk) return;          // rejected row, or a unit reserved for appends
+    const int r_end = min(kk, key0 + unit_slots);
     const int cap = kk + T_max;
-    const int64_t so = dev.slot_off[bl];
-    uint4* kd = reinterpret_cast<uint4*>(dev.kv + ((so * 2 * Hkv) + (int64_t)hkv * cap) * ROWBYTES);
+    uint4* kd = reinterpret_cast<uint4*>(dev.kv + it.kbase * elem_bytes);
     uint4* vd = kd + (int64_t)Hkv * cap * LPR;
-    const uint4* ks = reinterpret_cast<const uint4*>(k_full + (size_t)row * m * ROWBYTES);
-    const uint4* vs = reinterpret_cast<const uint4*>(v_full + (size_t)row * m * ROWBYTES);
-    const int32_t* idx = dev.idx + so * Hkv + (int64_t)hkv * cap;
+    const uint4* ks = reinterpret_cast<const uint4*>(k_full + (size_t)it.row_abs * m * ROWBYTES);
+    const uint4* vs = reinterpret_cast<const uint4*>(v_full + (size_t)it.row_abs * m * ROWBYTES);
+    const int32_t* idx = dev.idx + it.idx_base;
     const int c = threadIdx.x % LPR, sub = threadIdx.x / LPR;
-    for (int r0 = blockIdx.x * RPB * U; r0 < kk; r0 += gridDim.x * RPB * U) {
-        uint4 a[U], b[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = r0 + u * RPB + sub;
-            if (r < kk) {
-                const int64_t j = idx[r];
-                a[u] = ks[j * LPR + c];
-                b[u] = vs[j * LPR + c];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int r = r0 + u * RPB + sub;
-            if (r < kk) {
-                kd[(int64_t)r * LPR + c] = a[u];
-                vd[(int64_t)r * LPR + c] = b[u];
-            }
-        }
+    int r = key0 + sub;
+    int32_t jn = r < r_end ? idx[r] : 0;
+    for (; r < r_end; r += RPB) {
+        const uint4 a = ks[(int64_t)jn * LPR + c];
+        const uint4 b = vs[(int64_t)jn * LPR + c];
+        jn = r + RPB < r_end ? idx[r + RPB] : 0;
+        kd[(int64_t)r * LPR + c] = a;
+        vd[(int64_t)r * LPR + c] = b;
     }
 }
 
@@ -259,14 +275,13 @@ hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const in
                                c.max_items, c.dev);
     select_kernel<<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, idx_out);
     const int rowbytes = s.d * (s.dtype == VLC_F32 ? 4 : 2);
-    int gx = (4096 + rows - 1) / rows;
-    gx = gx < 1 ? 1 : (gx > 32 ? 32 : gx);
-    dim3 grid(gx, rows);
+    const int es = s.dtype == VLC_F32 ? 4 : 2;
+    const unsigned grid = (unsigned)c.max_items;
     const char* kf = (const char*)k_full;
     const char* vf = (const char*)v_full;
-    if (rowbytes == 128) gather_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.Hkv, s.m, c.T_max);
-    else if (rowbytes == 256) gather_kernel<256><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.Hkv, s.m, c.T_max);
-    else gather_kernel<512><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.Hkv, s.m, c.T_max);
+    if (rowbytes == 128) gather_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
+    else if (rowbytes == 256) gather_kernel<256><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
+    else gather_kernel<512><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
     return hipGetLastError();
 }
 
