@@ -113,17 +113,24 @@ def main() -> int:
     dec_launch_us = float(np.mean(dec_ms)) * 1e3 / T                    # mean duration of one ragged all-layer launch
     dec_us_layer_step = dec_launch_us / cfg.L
 
-    # ---- the same decode work issued as one launch per layer (how a model would call it)
+    # ---- the same decode work issued as one launch per layer (how a model would call it).  The T * L
+    # launches are recorded into a HIP graph so that the figure is the kernels', not the interpreter's.
     path.compress(q_win, k, v, sm)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for t in range(T):
+            for l in range(cfg.L):
+                path.decode(l, l + 1, dq[t, l], dk[t, l], dv[t, l], sm, out[t, l])
+    graph.replay()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for t in range(T):
-        for l in range(cfg.L):
-            path.decode(l, l + 1, dq[t, l], dk[t, l], dv[t, l], sm, out[t, l])
+    graph.replay()
     e1.record()
     torch.cuda.synchronize()
     per_layer_us = e0.elapsed_time(e1) * 1e3 / (T * cfg.L)
+    del graph
 
     # ---- algorithmic bytes of one decode launch (Kc + Vc rows read once, q / out / appended rows)
     kk = path.k.cpu().numpy().astype(np.int64)                            # [B, L]

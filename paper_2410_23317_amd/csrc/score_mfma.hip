@@ -312,7 +312,12 @@ Plan make_plan(const vlc_shape& s) {
     else { p.waves = 16; p.rb = 1; }
     const int groups = s.B * s.L * s.Hkv;
     const int chunks = (s.m + kChunk - 1) / kChunk;
-    int ns = (2048 + groups - 1) / groups;          // aim for a couple of thousand blocks
+    // Splits of the key range per KV group.  Measured on the 7B and 34B shapes: about one resident
+    // round of blocks (768 four-wave blocks fit the chip) beats finer splits, whose per-block
+    // prologue (Q' fragments, row statistics) is not hidden; with a thousand or more groups two
+    // splits even out the last round.
+    int ns = (768 + groups - 1) / groups;
+    if (ns == 1 && chunks >= 16) ns = 2;
     if (ns > chunks) ns = chunks;
     if (ns < 1) ns = 1;
     const int cps = (chunks + ns - 1) / ns;

@@ -2,8 +2,8 @@
 // (paper Sec. 2.2 top-k set, Sec. 4.2) and the copy of the surviving K/V rows into the contiguous,
 // ragged per-layer cache (App. A.4).  Three kernels on one stream:
 //   layout : validates k[b][l], prefix-sums the slab offsets of a request's layers
-//   select : radix-select of the k-th largest score, then an ordered compaction that emits the
-//            kept positions ascending (ties to the lower position)
+//   select : radix-select of the k-th largest score over keys held in registers, then an ordered
+//            compaction that emits the kept positions ascending (ties to the lower position)
 //   gather : one block per work-list unit streams the kept rows of K and V into the slabs
 #include "common.h"
 #include "internal.h"
@@ -126,10 +126,43 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 constexpr int kSelThreads = 512;
 constexpr int kSelWaves = kSelThreads / 64;
 
+// Visit the candidates of this wave's segment [j0, j1): f(position, key, inside).  Every lane calls f
+// the same number of times, so f may hold wave-wide ballots.  With NK > 0 the keys come from the
+// registers filled at the start of the kernel, else they are streamed from memory four at a time.
+template <int NK, typename F>
+__device__ __forceinline__ void for_keys(const uint32_t (&key)[NK > 0 ? NK : 1], const float* __restrict__ s,
+                                         int j0, int j1, int lane, F f) {
+    if constexpr (NK > 0) {
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int j = j0 + i * 64 + lane;
+            f(j, key[i], j < j1);
+        }
+    } else {
+        for (int jb = j0; jb < j1; jb += 4 * 64) {
+            float v[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) v[x] = s[min(jb + x * 64 + lane, j1 - 1)];    // unconditional: no wait between loads
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int j = jb + x * 64 + lane;
+                f(j, order_key(v[x]), j < j1);
+            }
+        }
+    }
+}
+
+// One block per (request, layer, KV head) row.  Each wave owns a contiguous segment of the row and,
+// when the segment fits NK values per lane, keeps its keys in registers: the scores are then read
+// from memory once for the four digit passes, the count and the ordered emission.
+// The digit histogram is kept in SUB interleaved copies: lane l adds into copy l % SUB, which lies in a
+// bank of its own, so that lanes of a wave with equal digits do not serialise on one LDS word.
+template <int NK>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, CacheDev dev,
                                                              int Hkv, int m, int T_max, int n_recent,
                                                              int32_t* __restrict__ idx_out) {
-    __shared__ uint32_t hist[256];
+    constexpr int kSelSub = NK == 8 ? 4 : 16;                  // short rows: few adds, the clear and the sum dominate
+    __shared__ __align__(16) uint32_t hist[256 * kSelSub];
     __shared__ uint32_t sel_bin, sel_above;
     __shared__ uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
     const int row = blockIdx.x;
@@ -144,24 +177,68 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     int32_t* out = dev.idx + dev.slot_off[bl] * Hkv + (int64_t)hkv * cap;
     int32_t* out2 = idx_out ? idx_out + (size_t)row * m : nullptr;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seg = ((mc + kSelWaves - 1) / kSelWaves + 63) & ~63;
+    const int j0 = wave * seg, j1 = min(mc, j0 + seg);
 
+    uint32_t key[NK > 0 ? NK : 1];
+    if constexpr (NK > 0) {
+#pragma unroll
+        for (int i = 0; i < NK; ++i) {
+            const int j = j0 + i * 64 + lane;
+            // the address is clamped rather than the load predicated, so that the NK loads of a lane
+            // are all in flight together (a predicated load is followed by a wait for its value)
+            const uint32_t u = order_key(s[max(0, min(j, mc - 1))]);
+            key[i] = j < j1 ? u : 0u;
+        }
+    }
+
+    // The keys of a row usually share their leading bits (positive scores within a few binades), and a
+    // digit taken from shared bits would send every lane's LDS atomic to one or two bins.  The digit
+    // passes therefore start at the highest bit in which two keys of the row differ.
     uint32_t prefix = 0, mask = 0, remaining = (uint32_t)need;
     if (need > 0) {
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
-            if (tid < 256) hist[tid] = 0;
+        uint32_t all_and = 0xffffffffu, all_or = 0u;
+        for_keys<NK>(key, s, j0, j1, lane, [&](int, uint32_t u, bool in) {
+            if (in) { all_and &= u; all_or |= u; }
+        });
+        for (int o = 32; o >= 1; o >>= 1) {
+            all_and &= (uint32_t)__shfl_xor((int)all_and, o, 64);
+            all_or |= (uint32_t)__shfl_xor((int)all_or, o, 64);
+        }
+        if (lane == 0) { cnt_gt[wave] = all_and; cnt_eq[wave] = all_or; }
+        __syncthreads();
+        all_and = 0xffffffffu; all_or = 0u;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) { all_and &= cnt_gt[w]; all_or |= cnt_eq[w]; }
+        __syncthreads();
+        const uint32_t diff = all_and ^ all_or;
+        int bits_left = diff ? 32 - __clz((int)diff) : 0;          // low bits still to be resolved
+        mask = bits_left >= 32 ? 0u : ~((1u << bits_left) - 1u);
+        prefix = all_or & mask;
+        while (bits_left > 0) {
+            const int width = min(8, bits_left);
+            const int shift = bits_left - width;
+            const uint32_t dmask = (1u << width) - 1u;
+            for (int x = tid; x < 256 * kSelSub / 4; x += kSelThreads)
+                reinterpret_cast<uint4*>(hist)[x] = make_uint4(0, 0, 0, 0);
             __syncthreads();
-            for (int j = tid; j < mc; j += kSelThreads) {
-                const uint32_t u = order_key(s[j]);
-                if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
-            }
+            for_keys<NK>(key, s, j0, j1, lane, [&](int, uint32_t u, bool in) {
+                if (in && (u & mask) == prefix) atomicAdd(&hist[((u >> shift) & dmask) * kSelSub + (lane & (kSelSub - 1))], 1u);
+            });
             __syncthreads();
             if (wave == 0) {
                 // lane i owns bins 4i..4i+3; find the highest bin whose count, added to everything
                 // above it, reaches `remaining`
                 uint32_t c[4];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) c[x] = hist[lane * 4 + x];
+                for (int x = 0; x < 4; ++x) {
+                    c[x] = 0;
+#pragma unroll
+                    for (int q = 0; q < kSelSub / 4; ++q) {
+                        const uint4 h4 = reinterpret_cast<const uint4*>(hist)[(lane * 4 + x) * (kSelSub / 4) + q];
+                        c[x] += h4.x + h4.y + h4.z + h4.w;
+                    }
+                }
                 const uint32_t tot = c[0] + c[1] + c[2] + c[3];
                 uint32_t suf = tot;             // inclusive suffix sum over lanes >= this one
                 for (int o = 1; o < 64; o <<= 1) {
@@ -179,22 +256,20 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             }
             __syncthreads();
             prefix |= sel_bin << shift;
-            mask |= 0xffu << shift;
+            mask |= dmask << shift;
             remaining -= sel_above;            // those above are all kept; keep looking inside the bin
+            bits_left = shift;
             __syncthreads();
         }
     }
     // `prefix` is now the key of the need-th largest candidate; `remaining` of the candidates equal
     // to it are kept, lowest positions first.
-    const int seg = ((mc + kSelWaves - 1) / kSelWaves + 63) & ~63;
-    const int j0 = wave * seg, j1 = min(mc, j0 + seg);
     uint32_t gt = 0, eq = 0;
     if (need > 0) {
-        for (int j = j0 + lane; j < j1; j += 64) {
-            const uint32_t u = order_key(s[j]);
-            gt += (u > prefix) ? 1u : 0u;
-            eq += (u == prefix) ? 1u : 0u;
-        }
+        for_keys<NK>(key, s, j0, j1, lane, [&](int, uint32_t u, bool in) {
+            gt += (in && u > prefix) ? 1u : 0u;
+            eq += (in && u == prefix) ? 1u : 0u;
+        });
         gt = wave_allreduce_sum_u32(gt);
         eq = wave_allreduce_sum_u32(eq);
     }
@@ -204,10 +279,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         uint32_t gt_run = 0, eq_run = 0;
         for (int w = 0; w < wave; ++w) { gt_run += cnt_gt[w]; eq_run += cnt_eq[w]; }
         const unsigned long long lt_mask = (1ull << lane) - 1ull;
-        for (int jb = j0; jb < j1; jb += 64) {
-            const int j = jb + lane;
-            const bool in = j < j1;
-            const uint32_t u = in ? order_key(s[j]) : 0u;
+        for_keys<NK>(key, s, j0, j1, lane, [&](int j, uint32_t u, bool in) {
             const bool is_gt = in && (u > prefix);
             const bool is_eq = in && (u == prefix);
             const unsigned long long bg = __ballot(is_gt), be = __ballot(is_eq);
@@ -221,7 +293,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             }
             gt_run += (uint32_t)__popcll(bg);
             eq_run += (uint32_t)__popcll(be);
-        }
+        });
     }
     for (int x = tid; x < rcnt; x += kSelThreads) {     // forced recent window
         out[need + x] = mc + x;
@@ -273,7 +345,14 @@ hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const in
     const int rows = s.B * s.L * s.Hkv;
     layout_kernel<<<1, 256, 0, st>>>(k, s.B, s.L, s.Hkv, s.m, s.d, c.T_max, c.slots_per_request, c.unit_slots,
                                c.max_items, c.dev);
-    select_kernel<<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, idx_out);
+    // values per lane of a wave's segment (an eighth of the row, rounded up to whole wave loads)
+    const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
+#define VLC_SELECT(NK) select_kernel<NK><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, idx_out)
+    if (per_lane <= 8) VLC_SELECT(8);
+    else if (per_lane <= 24) VLC_SELECT(24);
+    else if (per_lane <= 64) VLC_SELECT(64);
+    else VLC_SELECT(0);
+#undef VLC_SELECT
     const int rowbytes = s.d * (s.dtype == VLC_F32 ? 4 : 2);
     const int es = s.dtype == VLC_F32 ? 4 : 2;
     const unsigned grid = (unsigned)c.max_items;

@@ -87,6 +87,25 @@ def test_topk_ties_extremes_and_recent_window():
     assert idx[0].cpu().numpy().tolist() == list(range(7)) and idx[1].cpu().numpy().tolist() == list(range(7))
 
 
+@pytest.mark.parametrize("m", [4096, 4097, 12288, 12289, 32768, 32769, 40001])
+def test_topk_row_lengths_around_the_register_resident_limits(m):
+    """The selection keeps a row's keys in registers up to 32768 positions (8, 24 or 64 per lane)
+    and streams longer rows; each variant, with heavy ties and a ragged tail, against the oracle."""
+    V = _V()
+    r = np.random.default_rng(m)
+    scores = np.empty((1, 1, 2, m), dtype=np.float32)
+    scores[0, 0, 0] = np.round(r.random(m), 3)                     # ~1000 distinct values: many ties at the cut
+    scores[0, 0, 1] = r.standard_normal(m) * 1e-3
+    for k, n_recent in [(m // 10, 0), (m - 1, 0), (257, 31)]:
+        cache, idx_out, K, Vv, view = _topk_case(V, scores, np.array([[k]]), n_recent, m, d=64)
+        V.vlc_cache_status(cache)
+        kc, vc, idx = view(cache, 0, 0)
+        for h in range(2):
+            want = O.topk(scores[0, 0, h].astype(np.float64), k, n_recent)
+            assert np.array_equal(idx[h].cpu().numpy(), want), (m, k, n_recent, h)
+            assert torch.equal(kc[h], K[0, 0, h][torch.from_numpy(want).cuda()])
+
+
 def test_device_side_errors_are_sticky_and_harmless():
     V = _V()
     m = 300
