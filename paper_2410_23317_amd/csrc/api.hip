@@ -169,7 +169,7 @@ vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alp
 
 struct ArenaPlan {
     vlc_cache_layout lay;
-    size_t items_off, layer_start_off, row_first_off, partials_off, counters_off;
+    size_t items_off, items2_off, layer_start_off, row_first_off, partials_off, counters_off;
     int32_t unit_slots;
     int64_t max_items;
 };
@@ -200,6 +200,7 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     lay->idx_off = off;         off = align_up(off + (size_t)s->B * spr * s->Hkv * sizeof(int32_t), 256);
     lay->scratch_off = off;
     plan->items_off = off;        off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
+    plan->items2_off = off;       off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
     plan->layer_start_off = off;  off = align_up(off + (size_t)(s->L + 1) * sizeof(int32_t), 256);
     plan->row_first_off = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
     plan->partials_off = off;     off = align_up(off + (size_t)plan->max_items * g * (s->d + 2) * sizeof(float), 256);
@@ -243,6 +244,7 @@ vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k
     c->dev.kv = c->arena + lay.kv_off;
     c->dev.idx = (int32_t*)(c->arena + lay.idx_off);
     c->dev.items = (vlc::WorkItem*)(c->arena + plan.items_off);
+    c->dev.items_by_size = (vlc::WorkItem*)(c->arena + plan.items2_off);
     c->dev.layer_item_start = (int32_t*)(c->arena + plan.layer_start_off);
     c->dev.row_item_first = (int32_t*)(c->arena + plan.row_first_off);
     c->dev.partials = (float*)(c->arena + plan.partials_off);

@@ -38,6 +38,7 @@ struct DecodeParams {
     void* out;
     const float* sm_scale;
     CacheDev dev;
+    const WorkItem* items;   // the work list this launch walks
     int B, L, Hq, Hkv, m;
     int layer_begin, n_layers, T_max;
     int appended;            // appends before this call
@@ -181,10 +182,10 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
         if (w >= P.dev.layer_item_start[P.layer_begin + P.n_layers]) return;
     }
     {
-        const WorkItem itv = P.dev.items[w];
+        const WorkItem itv = P.items[w];
         if (P.layer_begin == 0 && w >= P.dev.layer_item_start[P.n_layers]) return;
         const int kept = uniform(itv.kept), key0 = uniform(itv.key0), row_abs = uniform(itv.row_abs);
-        const int unit = uniform(itv.unit), ib = uniform(itv.b), il = uniform(itv.l);
+        const int unit = uniform(itv.unit), ib = uniform(itv.b), il = uniform(itv.l), canon = uniform(itv.canon);
         const int64_t kbase = uniform64(itv.kbase), idx_base = uniform64(itv.idx_base);
         const int lr = il - P.layer_begin;
         const int hkv = row_abs % P.Hkv;
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                 }
         }
         __syncthreads();
-        float* part = P.dev.partials + (size_t)w * G * DP;
+        float* part = P.dev.partials + (size_t)canon * G * DP;      // partials sit in the layer-major order
         for (int x = tid; x < G * D; x += 256) {
             const int h = x / D, e = x % D;
             float mt = -INFINITY;
@@ -432,7 +433,7 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                 sLast = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nu - 1) ? 1 : 0;
             __syncthreads();
             if (sLast) {
-                merge_partials<T, D, G, true>(P.dev.partials + (size_t)(w - unit) * G * DP, outp, nu, tid);
+                merge_partials<T, D, G, true>(P.dev.partials + (size_t)(canon - unit) * G * DP, outp, nu, tid);
                 if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
@@ -502,6 +503,12 @@ hipError_t launch_decode(const DecodeArgs& a) {
     DecodeParams P;
     P.q = a.q; P.k_new = a.k_new; P.v_new = a.v_new; P.out = a.out; P.sm_scale = a.sm_scale;
     P.dev = c.dev;
+    // A launch over all layers of a cache with more units than fit the chip at once (768 blocks)
+    // walks the size-class order, so that the blocks dispatched last are the short units.  When all
+    // units are resident together the order only moves the units of a row apart, which measured slower.
+    const int order = env_int("VLC_DECODE_ORDER", 0);                     // tuning knob: 1 layer-major, 2 size classes
+    const bool by_size = order == 2 || (order != 1 && c.max_items > 1536);
+    P.items = (a.layer_begin == 0 && a.n_layers == s.L && by_size) ? c.dev.items_by_size : c.dev.items;
     P.B = s.B; P.L = s.L; P.Hq = s.Hq; P.Hkv = s.Hkv; P.m = s.m;
     P.layer_begin = a.layer_begin; P.n_layers = a.n_layers; P.T_max = c.T_max;
     P.appended = a.appended;

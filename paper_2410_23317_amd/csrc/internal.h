@@ -14,8 +14,10 @@ constexpr int kMaxLayers = 1024;
 constexpr int kScoreChunk = 256;       // keys per block of the generic scoring sweeps
 
 // One block-unit of decode work: `unit_slots` consecutive cache slots of one (b, l, kv head) row.
-// Built on the device by vlc_topk_compact, ordered by (layer, request, kv head, unit) so that a
-// layer range is a contiguous slice of the list.
+// Built on the device by vlc_topk_compact in two orders: by (layer, request, kv head, unit), so that
+// a layer range is a contiguous slice of the list, and by size class (full units, then the partly
+// filled last units, then units that only hold slots reserved for appends) for launches over all
+// layers, where the blocks dispatched last should be the short ones.
 struct WorkItem {
     int32_t row_abs;                   // (b*L + l)*Hkv + hkv
     int32_t key0;                      // first slot of the unit
@@ -24,7 +26,8 @@ struct WorkItem {
     int64_t kbase;                     // element offset of the row's K slab inside the kv region
     int64_t idx_base;                  // offset of the row's kept-index list inside the idx region
     int32_t b, l;
-    int32_t pad[2];
+    int32_t canon;                     // index of this unit in the (layer, request, kv head, unit) order
+    int32_t pad;
 };
 static_assert(sizeof(WorkItem) == 48, "WorkItem layout");
 
@@ -34,7 +37,8 @@ struct CacheDev {                      // device pointers into the caller's aren
     int32_t* kept;                     // [B*L]
     char* kv;
     int32_t* idx;
-    WorkItem* items;                   // [max_items]
+    WorkItem* items;                   // [max_items], layer-major order
+    WorkItem* items_by_size;           // [max_items], the same units by size class
     int32_t* layer_item_start;         // [L+1]
     int32_t* row_item_first;           // [B*L*Hkv]
     float* partials;                   // [max_items][g][d + 2]

@@ -22,7 +22,9 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
     __shared__ int32_t sKept[kLayoutMaxBL];
     __shared__ int32_t sFirst[kLayoutMaxBL];        // first work item of (b, l), kv head 0
     __shared__ int64_t sSlot[kLayoutMaxBL];
-    __shared__ int64_t sScan[256];
+    __shared__ int64_t sScan[256], sScan2[256];
+    __shared__ int32_t sFullFirst[kLayoutMaxBL], sPartFirst[kLayoutMaxBL];
+    __shared__ int sTotals[2];
     __shared__ int sBad;
     const int tid = threadIdx.x;
     const int BL = B * L;
@@ -53,26 +55,32 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         }
     }
     __syncthreads();
-    // work list: units per row, exclusive prefix over (layer, request) in that order.  Each thread
-    // sums a run of consecutive entries, the run totals are scanned across the block, then every
-    // thread walks its run again from its offset.
+    // work list: units per row, exclusive prefix over (layer, request) in that order, for all units
+    // and separately for the full and the partly filled ones (the size-class order).  Each thread sums
+    // a run of consecutive entries, the run totals are scanned across the block, then every thread
+    // walks its run again from its offset.
     {
         const int per = (BL + 255) / 256;
         const int y0 = tid * per, y1 = min(BL, y0 + per);
-        int64_t run = 0;
+        int64_t run = 0, run2 = 0;              // run2 packs (full units << 32) | partly filled units
         for (int y = y0; y < y1; ++y) {
             const int kk = sKept[(y % B) * L + y / B];
             run += (int64_t)(kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1) * Hkv;
+            run2 += ((int64_t)(kk / unit_slots) * Hkv << 32) | (int64_t)((kk % unit_slots) ? Hkv : 0);
         }
         sScan[tid] = run;
+        sScan2[tid] = run2;
         __syncthreads();
         for (int o = 1; o < 256; o <<= 1) {
             const int64_t v = tid >= o ? sScan[tid - o] : 0;
+            const int64_t v2 = tid >= o ? sScan2[tid - o] : 0;
             __syncthreads();
             sScan[tid] += v;
+            sScan2[tid] += v2;
             __syncthreads();
         }
         const int64_t total = sScan[255];
+        if (tid == 0) { sTotals[0] = (int)(sScan2[255] >> 32); sTotals[1] = (int)(sScan2[255] & 0xffffffff); }
         if (total > max_items) {            // cannot happen for budgets that passed the capacity check
             if (tid == 0) {
                 set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
@@ -80,13 +88,16 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
             }
             for (int l = tid; l <= L; l += 256) dev.layer_item_start[l] = 0;
         } else {
-            int64_t acc = sScan[tid] - run;
+            int64_t acc = sScan[tid] - run, acc2 = sScan2[tid] - run2;
             for (int y = y0; y < y1; ++y) {
                 const int l = y / B, b = y % B;
                 const int kk = sKept[b * L + l];
                 if (b == 0) dev.layer_item_start[l] = (int)acc;
                 sFirst[b * L + l] = (int)acc;
+                sFullFirst[b * L + l] = (int)(acc2 >> 32);
+                sPartFirst[b * L + l] = (int)(acc2 & 0xffffffff);
                 acc += (int64_t)(kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1) * Hkv;
+                acc2 += ((int64_t)(kk / unit_slots) * Hkv << 32) | (int64_t)((kk % unit_slots) ? Hkv : 0);
             }
             if (tid == 0) dev.layer_item_start[L] = (int)total;
         }
@@ -97,22 +108,33 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         dev.slot_off[x] = sSlot[x];
     }
     if (sBad) return;
+    const int n_full = sTotals[0], n_part = sTotals[1];
     for (int x = tid; x < BL * Hkv; x += blockDim.x) {
         const int h = x % Hkv, bl = x / Hkv, b = bl / L, l = bl % L;
         const int kk = sKept[bl];
         const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
+        const int nfull = kk / unit_slots, npart = (kk % unit_slots) ? 1 : 0;
+        const int nres = nu - nfull - npart;
         const int cap = kk + T_max;
         const int64_t so = sSlot[bl];
         WorkItem it;
-        it.row_abs = x; it.kept = kk; it.b = b; it.l = l; it.pad[0] = it.pad[1] = 0;
+        it.row_abs = x; it.kept = kk; it.b = b; it.l = l; it.pad = 0;
         it.kbase = ((so * 2 * Hkv) + (int64_t)h * cap) * d;
         it.idx_base = so * Hkv + (int64_t)h * cap;
         const int w0 = sFirst[bl] + h * nu;
+        // units of neither class precede this row's in the list: all units before it minus full and part
+        const int res0 = n_full + n_part + (sFirst[bl] - sFullFirst[bl] - sPartFirst[bl]) + h * nres;
         dev.row_item_first[x] = w0;
         for (int u = 0; u < nu; ++u) {
             it.unit = u;
             it.key0 = u * unit_slots;
+            it.canon = w0 + u;
             dev.items[w0 + u] = it;
+            int ws;
+            if (u < nfull) ws = sFullFirst[bl] + h * nfull + u;
+            else if (u == nfull && npart) ws = n_full + sPartFirst[bl] + h;
+            else ws = res0 + (u - nfull - npart);
+            dev.items_by_size[ws] = it;
         }
     }
 }
