@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 METRIC = "KV compress ms/request; decode-attn µs/layer-step @10% budget; % HBM peak"
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes of one all-layer decode launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
+# counter reads for a plain 256 MiB copy), measured offline on the default run of a config: 10 % budget,
+# 100 decode steps.  The figures and the commands are in profiles/all_kernels_cfg*.md.
+MEASURED_DECODE_TRAFFIC_MIB = {1: 45.09 + 1.27, 2: 551.79 + 7.33}
 
 
 def main() -> int:
@@ -139,9 +143,11 @@ def main() -> int:
     io_bytes = cfg.B * cfg.L * (2 * cfg.Hq + 2 * cfg.Hkv) * cfg.d * es
     alg_bytes = kv_bytes + io_bytes
     achieved = alg_bytes / (dec_launch_us * 1e-6) / 1e9
+    default_run = alpha == (1, 10) and T == 100 and cfg.cid in MEASURED_DECODE_TRAFFIC_MIB
+    traffic = int(MEASURED_DECODE_TRAFFIC_MIB[cfg.cid] * 1048576) if default_run else None
     roofline = {"bound": "hbm", "kernel": "decode_kernel (one ragged launch over all layers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": int(alg_bytes), "launch_us": round(dec_launch_us, 3)}
 
     result = {
