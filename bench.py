@@ -20,6 +20,7 @@ if ROOT not in sys.path:
 
 METRIC = "KV compress ms/request; decode-attn µs/layer-step @10% budget; % HBM peak"
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_FLOPS = 2.5e15
 # HBM-side bytes of one all-layer decode launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # counter reads for a plain 256 MiB copy), measured offline on the default run of a config: 10 % budget,
 # 100 decode steps.  The figures and the commands are in profiles/all_kernels_cfg*.md.
@@ -95,7 +96,11 @@ def main() -> int:
 
     def one_step(ev=None):
         if ev: ev[0].record()
-        path.compress(q_win, k, v, sm)
+        path.score(q_win, k, sm)
+        if ev: ev[3].record()
+        path.sparsity()
+        path.allocate()
+        path.topk_compact(k, v)
         if ev: ev[1].record()
         path.decode_steps(0, cfg.L, T, dq, dk, dv, sm, out)      # T launches enqueued from one C loop
         if ev: ev[2].record()
@@ -104,7 +109,7 @@ def main() -> int:
         one_step()
     torch.cuda.synchronize()
     path.status()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     w0 = time.perf_counter()
     for i in range(args.steps):
@@ -136,6 +141,12 @@ def main() -> int:
     per_layer_us = e0.elapsed_time(e1) * 1e3 / (T * cfg.L)
     del graph
 
+    # ---- the two scoring sweeps of those steps: matrix-core utilisation of the window Q'K^T (2 tau d m flop
+    # per query head, request and layer, once per sweep) against the dense bf16 peak
+    score_ms = float(np.median([e[0].elapsed_time(e[3]) for e in events]))
+    score_flop = 2 * 2.0 * cfg.tau * cfg.d * cfg.m * cfg.Hq * cfg.B * cfg.L
+    mfma_util = score_flop / (score_ms * 1e-3) / MFMA_BF16_PEAK_FLOPS if cfg.dtype == "bf16" else None
+
     # ---- algorithmic bytes of one decode launch (Kc + Vc rows read once, q / out / appended rows)
     kk = path.k.cpu().numpy().astype(np.int64)                            # [B, L]
     mean_len = kk.sum() + cfg.B * cfg.L * (T + 1) / 2.0                   # sum over (b,l) of the mean slot count
@@ -162,6 +173,8 @@ def main() -> int:
                        "decode_attn_us_per_layer_step": round(dec_us_layer_step, 4),
                        "decode_attn_us_per_layer_step_one_launch_per_layer": round(per_layer_us, 4),
                        "decode_pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
+                       "score_ms_per_batch": round(score_ms, 4),
+                       "score_mfma_utilisation": None if mfma_util is None else round(mfma_util, 4),
                        "budgets_request0": kk[0].tolist(), "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
     }
