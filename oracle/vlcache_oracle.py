@@ -180,6 +180,15 @@ def topk(psi: np.ndarray, k: int, n_recent: int = 0) -> np.ndarray:
     return np.sort(chosen).astype(np.int64)
 
 
+def recent_count(k: int, num: int, den: int) -> int:
+    """Size of the forced recent window when it is a fixed fraction of the layer's budget
+    (Sec. 5 'Implementation Details': 10 % of the budget), rounded down: floor(k * num / den).
+    The paper does not say how the product is rounded; floor is this build's reading."""
+    if not (0 <= num <= den and den >= 1):
+        raise ValueError("fraction out of range")
+    return (int(k) * int(num)) // int(den)
+
+
 def compact(k: np.ndarray, v: np.ndarray, idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Survivors copied to contiguous memory in ascending position: Kc = K[idx], Vc = V[idx]."""
     return np.asarray(k)[idx].copy(), np.asarray(v)[idx].copy()

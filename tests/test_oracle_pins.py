@@ -223,6 +223,29 @@ def test_topk_recent_window():
     assert list(O.topk(psi, 3, n_recent=0)) == [0, 1, 2]
 
 
+def test_recent_window_as_a_fraction_of_the_budget():
+    # Sec. 5 fixes the recent window at 10 % of the budget: 10 % of 294 tokens is 29.4 -> 29 whole tokens
+    assert O.recent_count(294, 1, 10) == 29
+    assert O.recent_count(9, 1, 10) == 0 and O.recent_count(10, 1, 10) == 1
+    assert O.recent_count(77, 1, 1) == 77 and O.recent_count(77, 0, 5) == 0
+    # never more than the budget, monotone in the budget
+    r = np.random.default_rng(0)
+    for _ in range(200):
+        k, den = int(r.integers(1, 5000)), int(r.integers(1, 50))
+        num = int(r.integers(0, den + 1))
+        c = O.recent_count(k, num, den)
+        assert 0 <= c <= k and c <= O.recent_count(k + 1, num, den)
+        assert c * den <= k * num < (c + 1) * den
+    # with the window in force the kept set is the last c positions plus the best of the rest (brute force)
+    psi = r.random(40)
+    k = 20
+    c = O.recent_count(k, 1, 10)
+    want = sorted(list(range(40 - c, 40)) + sorted(range(40 - c), key=lambda j: (-psi[j], j))[: k - c])
+    assert list(O.topk(psi, k, c)) == want
+    with pytest.raises(ValueError):
+        O.recent_count(5, 3, 2)
+
+
 def test_compact_is_a_gather():
     _, k, v = rand_case(2, m=19)
     idx = np.array([0, 3, 4, 18])
