@@ -173,6 +173,17 @@ vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t
                             int32_t* idx_out, vlc_stream stream);
 
 /*
+ * vlc_topk_compact_recent_frac -- vlc_topk_compact with the forced recent window given as a
+ * fraction of each layer's own budget (paper Sec. 5, implementation details: the recent window is
+ * 10 % of the budget): n_recent[b][l] = floor(k[b][l] * recent_num / recent_den), computed on the
+ * device from the same k array.  0 <= recent_num <= recent_den, recent_den >= 1
+ * (VLC_ERR_INVALID_ARG otherwise); all other arguments, layouts and errors as vlc_topk_compact.
+ */
+vlc_status vlc_topk_compact_recent_frac(vlc_cache* cache, const float* scores, const int32_t* k,
+                                        int32_t recent_num, int32_t recent_den, const void* k_full,
+                                        const void* v_full, int32_t* idx_out, vlc_stream stream);
+
+/*
  * vlc_decode_attn -- one decode step of GQA attention over the compressed cache (paper
  * Sec. 2.1 decoding phase), for layers [layer_begin, layer_end).  If k_new != NULL the new
  * key/value of every (b, hkv) is appended first and attended; nothing is evicted.

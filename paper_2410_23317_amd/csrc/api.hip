@@ -275,18 +275,33 @@ vlc_status vlc_cache_status(vlc_cache* cache, vlc_stream stream) {
     return (vlc_status)st[0];
 }
 
-vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t* k, int32_t n_recent,
-                            const void* k_full, const void* v_full, int32_t* idx_out, vlc_stream stream) {
-    if (!cache) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: cache is NULL");
+static vlc_status topk_compact_common(const char* who, vlc_cache* cache, const float* scores, const int32_t* k,
+                                      int32_t n_recent, int32_t recent_num, int32_t recent_den, const void* k_full,
+                                      const void* v_full, int32_t* idx_out, vlc_stream stream) {
+    if (!cache) return fail(VLC_ERR_INVALID_ARG, "%s: cache is NULL", who);
     if (!scores || !k || !k_full || !v_full)
-        return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: scores, k, k_full and v_full must not be NULL");
-    if (n_recent < 0) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: n_recent = %d is negative", n_recent);
+        return fail(VLC_ERR_INVALID_ARG, "%s: scores, k, k_full and v_full must not be NULL", who);
     hipStream_t hs = (hipStream_t)stream;
-    hipError_t e = vlc::launch_topk_compact(*cache, scores, k, n_recent, k_full, v_full, idx_out, hs);
-    if (e != hipSuccess) return hip_fail(e, "vlc_topk_compact");
+    hipError_t e = vlc::launch_topk_compact(*cache, scores, k, n_recent, recent_num, recent_den, k_full, v_full, idx_out, hs);
+    if (e != hipSuccess) return hip_fail(e, who);
     cache->compacted = true;
     memset(cache->appended, 0, sizeof(cache->appended));
     return VLC_OK;
+}
+
+vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t* k, int32_t n_recent,
+                            const void* k_full, const void* v_full, int32_t* idx_out, vlc_stream stream) {
+    if (n_recent < 0) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: n_recent = %d is negative", n_recent);
+    return topk_compact_common("vlc_topk_compact", cache, scores, k, n_recent, 0, 0, k_full, v_full, idx_out, stream);
+}
+
+vlc_status vlc_topk_compact_recent_frac(vlc_cache* cache, const float* scores, const int32_t* k, int32_t recent_num,
+                                        int32_t recent_den, const void* k_full, const void* v_full,
+                                        int32_t* idx_out, vlc_stream stream) {
+    if (recent_den < 1 || recent_num < 0 || recent_num > recent_den)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact_recent_frac: fraction %d/%d is outside [0, 1]", recent_num, recent_den);
+    return topk_compact_common("vlc_topk_compact_recent_frac", cache, scores, k, 0, recent_num, recent_den, k_full, v_full,
+                               idx_out, stream);
 }
 
 vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,

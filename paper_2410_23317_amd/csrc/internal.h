@@ -93,9 +93,10 @@ hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t B_to
                            int32_t* k_out, float* beta_out, hipStream_t st);
 
 // ---- eviction ----
+// recent_den > 0: the recent window is floor(k * recent_num / recent_den) per (b, l), n_recent is ignored
 hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const int32_t* k,
-                               int32_t n_recent, const void* k_full, const void* v_full,
-                               int32_t* idx_out, hipStream_t st);
+                               int32_t n_recent, int32_t recent_num, int32_t recent_den,
+                               const void* k_full, const void* v_full, int32_t* idx_out, hipStream_t st);
 
 // ---- decode ----
 struct DecodeArgs {

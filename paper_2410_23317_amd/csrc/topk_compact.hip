@@ -182,6 +182,7 @@ __device__ __forceinline__ void for_keys(const uint32_t (&key)[NK > 0 ? NK : 1],
 template <int NK>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, CacheDev dev,
                                                              int Hkv, int m, int T_max, int n_recent,
+                                                             int recent_num, int recent_den,
                                                              int32_t* __restrict__ idx_out) {
     constexpr int kSelSub = NK == 8 ? 4 : 16;                  // short rows: few adds, the clear and the sum dominate
     __shared__ __align__(16) uint32_t hist[256 * kSelSub];
@@ -191,7 +192,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     const int hkv = row % Hkv, bl = row / Hkv;
     const int kk = dev.kept[bl];
     if (kk == 0) return;
-    const int rcnt = min(max(n_recent, 0), kk);
+    // forced recent window: a count, or a fraction of this layer's budget (Sec. 5: 10 % of the budget)
+    const int rcnt = recent_den > 0 ? (int)((int64_t)kk * recent_num / recent_den) : min(max(n_recent, 0), kk);
     const int need = kk - rcnt;                // picked by score among positions [0, mc)
     const int mc = m - rcnt;
     const int cap = kk + T_max;
@@ -362,14 +364,15 @@ __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_
 }  // namespace
 
 hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const int32_t* k, int32_t n_recent,
-                               const void* k_full, const void* v_full, int32_t* idx_out, hipStream_t st) {
+                               int32_t recent_num, int32_t recent_den, const void* k_full, const void* v_full,
+                               int32_t* idx_out, hipStream_t st) {
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
     layout_kernel<<<1, 256, 0, st>>>(k, s.B, s.L, s.Hkv, s.m, s.d, c.T_max, c.slots_per_request, c.unit_slots,
                                c.max_items, c.dev);
     // values per lane of a wave's segment (an eighth of the row, rounded up to whole wave loads)
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_SELECT(NK) select_kernel<NK><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, idx_out)
+#define VLC_SELECT(NK) select_kernel<NK><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, recent_num, recent_den, idx_out)
     if (per_lane <= 8) VLC_SELECT(8);
     else if (per_lane <= 24) VLC_SELECT(24);
     else if (per_lane <= 64) VLC_SELECT(64);

@@ -21,9 +21,11 @@ class VLCachePath:
     """Holds the output buffers of the compression stages and the compressed cache of one batch."""
 
     def __init__(self, shape: V.vlc_shape, alpha: Tuple[int, int] = (1, 10), p: float = 0.01,
-                 T_max: int = 128, n_recent: int = 0, device: str = "cuda", want_idx: bool = False):
+                 T_max: int = 128, n_recent: int = 0, device: str = "cuda", want_idx: bool = False,
+                 recent_frac: Optional[Tuple[int, int]] = None):
         s = shape
         self.shape, self.alpha, self.p, self.T_max, self.n_recent = s, alpha, float(p), int(T_max), int(n_recent)
+        self.recent_frac = recent_frac        # (num, den): recent window = floor(k_l * num / den) per layer
         dev = torch.device(device)
         f32, i32 = torch.float32, torch.int32
         self.scores = torch.empty((s.B, s.L, s.Hkv, s.m), dtype=f32, device=dev)
@@ -51,8 +53,12 @@ class VLCachePath:
         V.vlc_allocate(self.shape, self.nnz, self.alpha[0], self.alpha[1], self.k, self.beta)
 
     def topk_compact(self, k_full, v_full, k: Optional[torch.Tensor] = None) -> None:
-        V.vlc_topk_compact(self.cache, self.scores, self.k if k is None else k, self.n_recent, k_full, v_full,
-                           self.idx_out)
+        kk = self.k if k is None else k
+        if self.recent_frac is not None:
+            V.vlc_topk_compact_recent_frac(self.cache, self.scores, kk, self.recent_frac[0], self.recent_frac[1],
+                                           k_full, v_full, self.idx_out)
+        else:
+            V.vlc_topk_compact(self.cache, self.scores, kk, self.n_recent, k_full, v_full, self.idx_out)
 
     def compress(self, q_win, k, v, sm_scale) -> None:
         self.score(q_win, k, sm_scale)

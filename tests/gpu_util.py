@@ -95,17 +95,18 @@ def out_tol(cfg):
 
 
 def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, requests_to_check=None, per_layer_decode=False,
-                  dev=None):
+                  dev=None, recent_frac=None):
     """Whole path on the GPU; oracle on every (or the listed) request/layer."""
     import paper_2410_23317_amd as V
     from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
 
     print(f"[case] cfg={cfg.name} cid={cfg.cid} m={cfg.m} tau={cfg.tau} d={cfg.d} g={cfg.g} alpha={alpha} "
-          f"steps={n_steps} n_recent={n_recent}", flush=True)
+          f"steps={n_steps} n_recent={n_recent} recent_frac={recent_frac}", flush=True)
     shape = make_shape(cfg)
     if dev is None:
         dev = upload(cfg)
-    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=max(n_steps, 1), n_recent=n_recent, want_idx=True)
+    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=max(n_steps, 1), n_recent=n_recent, want_idx=True,
+                       recent_frac=recent_frac)
     path.compress(dev["q_win"], dev["k"], dev["v"], dev["sm_scale"])
     path.status()
     torch.cuda.synchronize()
@@ -149,7 +150,8 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
             kc, vc, idx = cache_layer_view(path.cache, b, l)
             kc, vc, idx = kc.float().cpu().numpy(), vc.float().cpu().numpy(), idx.cpu().numpy()
             for h in range(cfg.Hkv):
-                swaps += check_topk(idx[h], psi[h], int(kk[b, l]), what + f" hkv={h} topk", n_recent=n_recent)
+                nr = n_recent if recent_frac is None else O.recent_count(int(kk[b, l]), *recent_frac)
+                swaps += check_topk(idx[h], psi[h], int(kk[b, l]), what + f" hkv={h} topk", n_recent=nr)
                 assert np.array_equal(path.idx_out[b, l, h, : kk[b, l]].cpu().numpy(), idx[h])
                 assert np.array_equal(kc[h], t["k"][h][idx[h]]), what + " gathered K rows"
                 assert np.array_equal(vc[h], t["v"][h][idx[h]]), what + " gathered V rows"

@@ -86,6 +86,9 @@ def test_cache_bookkeeping_errors(V):
     assert V.lib.vlc_decode_attn(None, 0, 1, 1, None, None, None, 1, None) == V.VLC_ERR_INVALID_ARG
     assert V.lib.vlc_topk_compact(h, None, 1, 0, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
     assert V.lib.vlc_topk_compact(h, 1, 1, -1, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    for num, den in ((1, 0), (-1, 10), (11, 10)):                       # recent fraction outside [0, 1]
+        assert V.lib.vlc_topk_compact_recent_frac(h, 1, 1, num, den, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_topk_compact_recent_frac(h, None, 1, 1, 10, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
     V.lib.vlc_cache_destroy(h)
 
 

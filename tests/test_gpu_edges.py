@@ -87,6 +87,31 @@ def test_topk_ties_extremes_and_recent_window():
     assert idx[0].cpu().numpy().tolist() == list(range(7)) and idx[1].cpu().numpy().tolist() == list(range(7))
 
 
+def test_recent_fraction_extremes():
+    """Fraction 0 keeps nothing unconditionally, fraction 1 keeps exactly the last k positions."""
+    V = _V()
+    from paper_2410_23317_amd.pipeline import cache_layer_view
+    m, d = 500, 64
+    r = np.random.default_rng(11)
+    scores = r.random((1, 2, 2, m)).astype(np.float32)
+    kk = np.array([[37, 120]])
+    shape = V.make_shape(1, 2, 2, 2, d, m, 1, "f32")
+    K = torch.randn((1, 2, 2, m, d)).cuda()
+    for num, den in ((0, 1), (1, 1), (1, 3)):
+        cache = V.vlc_cache_create(shape, 2, int(kk.sum()))
+        V.vlc_topk_compact_recent_frac(cache, torch.from_numpy(scores).cuda(), torch.from_numpy(kk.astype(np.int32)).cuda(),
+                                       num, den, K, K, None)
+        V.vlc_cache_status(cache)
+        for l in range(2):
+            _, _, idx = cache_layer_view(cache, 0, l)
+            c = O.recent_count(int(kk[0, l]), num, den)
+            for h in range(2):
+                want = O.topk(scores[0, l, h].astype(np.float64), int(kk[0, l]), c)
+                assert np.array_equal(idx[h].cpu().numpy(), want), (num, den, l, h)
+                if (num, den) == (1, 1):
+                    assert want.tolist() == list(range(m - int(kk[0, l]), m))
+
+
 @pytest.mark.parametrize("m", [4096, 4097, 12288, 12289, 32768, 32769, 40001])
 def test_topk_row_lengths_around_the_register_resident_limits(m):
     """The selection keeps a row's keys in registers up to 32768 positions (8, 24 or 64 per lane)

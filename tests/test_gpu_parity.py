@@ -43,6 +43,22 @@ def test_recent_window_variant():
     run_and_check(cfg, (1, 5), 2, n_recent=8)
 
 
+def test_recent_window_as_a_tenth_of_each_layer_budget():
+    """The comparison setting of Sec. 5: the recent window is 10 % of the (per-layer) budget."""
+    cfg = W.custom_config(cid=96, name="recent-frac", dtype="bf16", d=128, Hq=8, Hkv=2, m=900, tau=16, lead_text=8,
+                          n_visual=860, L=4, B=2, sinks=4, alphas=((1, 5),))
+    run_and_check(cfg, (1, 5), 2, recent_frac=(1, 10))
+
+
+@pytest.mark.parametrize("w", [8, 50])
+def test_fixed_sliding_window_scoring_policy(w):
+    """The accumulated sliding-window policy of Sec. 3.2 is the same computation with a fixed,
+    prompt-independent window w in place of the post-vision length tau (here tau would be 24)."""
+    cfg = W.custom_config(cid=97, name=f"sliding-w{w}", dtype="bf16", d=128, Hq=8, Hkv=2, m=640, tau=w, lead_text=16,
+                          n_visual=600, L=2, B=1, sinks=4, alphas=((1, 10),))
+    run_and_check(cfg, (1, 10), 2, recent_frac=(1, 10))
+
+
 def test_cfg1_7b_shape_all_layers():
     cfg = W.CONFIGS[1]
     run_and_check(cfg, cfg.alphas[0], 4)
