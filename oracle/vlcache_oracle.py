@@ -19,11 +19,14 @@ equal logits give harmonic-number scores; one dominant key per row gives nnz = t
 two-level logits give a counted nnz; equal sparsity gives equal budgets; the
 worked two-layer budget example; TopK equals a full sort; decode equals a library
 scaled-dot-product attention; full-budget decode equals uncompressed attention;
-every routine equals the pure-loop brute force on tiny inputs.
+every routine equals the pure-loop brute force on tiny inputs; the decode-query attention equals
+a library softmax; CacheHitRate is 1 for the optimal policy, 0 for a disjoint set, k/m-bounded
+and equal to a brute-force set intersection.
 
 Parity unpinned by the paper (self-consistency only): the reduction of the g query
-heads of a GQA group into one KV-head score (sum), the forced recent window, and
-the integer apportionment of budgets into token counts.
+heads of a GQA group into one KV-head score (sum; also used for the decode-query attention of
+CacheHitRate), the forced recent window and its rounding, and the integer apportionment of budgets
+into token counts.
 """
 from __future__ import annotations
 
@@ -192,6 +195,34 @@ def recent_count(k: int, num: int, den: int) -> int:
 def compact(k: np.ndarray, v: np.ndarray, idx: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     """Survivors copied to contiguous memory in ascending position: Kc = K[idx], Vc = V[idx]."""
     return np.asarray(k)[idx].copy(), np.asarray(v)[idx].copy()
+
+
+# --------------------------------------------------------------------------------------
+# CacheHitRate  (Def. 3.1)
+# --------------------------------------------------------------------------------------
+
+def decode_query_attention(q_next: np.ndarray, k: np.ndarray, scale: float) -> np.ndarray:
+    """A_{m+1} of Def. 3.1, per KV head: softmax over all m prompt keys of the first decode
+    query's logits, summed over the g query heads of the group.  q_next [Hq, d], k [Hkv, m, d]
+    -> [Hkv, m]."""
+    q = np.asarray(q_next, dtype=np.float64)
+    kk = np.asarray(k, dtype=np.float64)
+    Hq, Hkv = q.shape[0], kk.shape[0]
+    g = Hq // Hkv
+    out = np.zeros((Hkv, kk.shape[1]))
+    for h in range(Hq):
+        s = (kk[h // g] @ q[h]) * float(scale)
+        e = np.exp(s - s.max())
+        out[h // g] += e / e.sum()
+    return out
+
+
+def cache_hit_rate(psi_star: np.ndarray, kept: np.ndarray, k: int) -> Tuple[int, float]:
+    """Def. 3.1: S* = the k positions with the largest psi_star (ties to the lower position),
+    hits = |kept ∩ S*|, CacheHitRate = hits / |S*|.  `kept` are the positions a policy preserved."""
+    s_star = set(topk(psi_star, int(k)).tolist())
+    hits = len(s_star.intersection(int(j) for j in np.asarray(kept).tolist()))
+    return hits, hits / float(len(s_star))
 
 
 # --------------------------------------------------------------------------------------

@@ -246,6 +246,42 @@ def test_recent_window_as_a_fraction_of_the_budget():
         O.recent_count(5, 3, 2)
 
 
+def test_decode_query_attention_is_a_library_softmax_summed_over_the_group():
+    r = np.random.default_rng(8)
+    Hq, Hkv, m, d = 6, 2, 37, 16
+    q, k = r.standard_normal((Hq, d)), r.standard_normal((Hkv, m, d))
+    a = O.decode_query_attention(q, k, 0.3)
+    want = np.zeros((Hkv, m))
+    for h in range(Hq):
+        want[h // 3] += torch.softmax(torch.from_numpy(k[h // 3] @ q[h] * 0.3), dim=0).numpy()
+    np.testing.assert_allclose(a, want, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(a.sum(1), 3.0, rtol=1e-12)
+    # the same numbers as the window scoring with a one-row window placed after the prompt's last key:
+    # row 0 of a tau = 1 window sees every key (Alg. 1 region i + m - tau >= j)
+    psi, *_ = O.score(q[:, None, :], k, 0.3)
+    np.testing.assert_allclose(a, psi, rtol=1e-12)
+
+
+def test_cache_hit_rate_definition():
+    r = np.random.default_rng(9)
+    m, k = 60, 15
+    star = r.random(m)
+    best = O.topk(star, k)
+    assert O.cache_hit_rate(star, best, k) == (k, 1.0)                       # the optimal policy hits everything
+    rest = np.setdiff1d(np.arange(m), best)[:k]
+    assert O.cache_hit_rate(star, rest, k) == (0, 0.0)                       # a disjoint set hits nothing
+    assert O.cache_hit_rate(star, np.arange(m), m) == (m, 1.0)               # full budget
+    for _ in range(50):                                                      # brute-force set intersection
+        kept = r.choice(m, size=k, replace=False)
+        order = sorted(range(m), key=lambda j: (-star[j], j))[:k]
+        hits = len(set(order) & set(kept.tolist()))
+        assert O.cache_hit_rate(star, kept, k) == (hits, hits / k)
+    # ties at the cut go to the lower position
+    tied = np.array([1.0, 0.5, 0.5, 0.5, 0.0])
+    assert O.cache_hit_rate(tied, np.array([0, 1]), 2) == (2, 1.0)
+    assert O.cache_hit_rate(tied, np.array([0, 3]), 2) == (1, 0.5)
+
+
 def test_compact_is_a_gather():
     _, k, v = rand_case(2, m=19)
     idx = np.array([0, 3, 4, 18])
