@@ -147,6 +147,13 @@ def main() -> int:
     score_flop = 2 * 2.0 * cfg.tau * cfg.d * cfg.m * cfg.Hq * cfg.B * cfg.L
     mfma_util = score_flop / (score_ms * 1e-3) / MFMA_BF16_PEAK_FLOPS if cfg.dtype == "bf16" else None
 
+    # ---- CacheHitRate (Def. 3.1) of the compressed cache against the first decode query, a quality figure
+    # that needs no dataset: mean over (b, l, kv head) of |kept ∩ top-k of the decode query's attention| / k
+    path.compress(q_win, k, v, sm)
+    _, rate, _ = path.hit_rate(dq[0].permute(1, 0, 2, 3).contiguous(), k, sm)
+    torch.cuda.synchronize()
+    hit_rate_mean = float(rate.mean().item())
+
     # ---- algorithmic bytes of one decode launch (Kc + Vc rows read once, q / out / appended rows)
     kk = path.k.cpu().numpy().astype(np.int64)                            # [B, L]
     mean_len = kk.sum() + cfg.B * cfg.L * (T + 1) / 2.0                   # sum over (b,l) of the mean slot count
@@ -175,6 +182,7 @@ def main() -> int:
                        "decode_pct_hbm_peak": round(100 * achieved / HBM_PEAK_GBS, 2),
                        "score_ms_per_batch": round(score_ms, 4),
                        "score_mfma_utilisation": None if mfma_util is None else round(mfma_util, 4),
+                       "cache_hit_rate_mean": round(hit_rate_mean, 4),
                        "budgets_request0": kk[0].tolist(), "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
     }

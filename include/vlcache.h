@@ -184,6 +184,21 @@ vlc_status vlc_topk_compact_recent_frac(vlc_cache* cache, const float* scores, c
                                         const void* v_full, int32_t* idx_out, vlc_stream stream);
 
 /*
+ * vlc_cache_hit_rate -- CacheHitRate of paper Def. 3.1 for the set the cache holds.  For every
+ * (b,l,hkv): S* = the k[b][l] positions with the largest scores_star (ties to the lower position,
+ * no recent window), hits = |kept positions of the cache ∩ S*|, rate = hits / k[b][l].
+ * scores_star is the attention of the first decode query over the m prompt keys, summed over the
+ * query heads of the KV group: vlc_score on a shape with tau = 1 and q_win = that query computes it
+ * (a one-row window placed at the last position sees every key).  Positions appended by decode steps
+ * are not counted.
+ *
+ * scores_star [B,L,Hkv,m] float in;  hits_out [B,L,Hkv] int32 out;  rate_out [B,L,Hkv] float out or NULL.
+ * VLC_ERR_INVALID_ARG if the cache has not been filled; rows of a rejected request report 0.
+ */
+vlc_status vlc_cache_hit_rate(vlc_cache* cache, const float* scores_star, int32_t* hits_out,
+                              float* rate_out, vlc_stream stream);
+
+/*
  * vlc_decode_attn -- one decode step of GQA attention over the compressed cache (paper
  * Sec. 2.1 decoding phase), for layers [layer_begin, layer_end).  If k_new != NULL the new
  * key/value of every (b, hkv) is appended first and attended; nothing is evicted.

@@ -69,6 +69,8 @@ def _load() -> C.CDLL:
     lib.vlc_topk_compact.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp]
     lib.vlc_topk_compact_recent_frac.restype = C.c_int
     lib.vlc_topk_compact_recent_frac.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.vlc_cache_hit_rate.restype = C.c_int
+    lib.vlc_cache_hit_rate.argtypes = [vp, vp, vp, vp, vp]
     lib.vlc_decode_attn.restype = C.c_int
     lib.vlc_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.vlc_decode_attn_steps.restype = C.c_int
@@ -184,6 +186,10 @@ def vlc_topk_compact(cache: Cache, scores, k, n_recent, k_full, v_full, idx_out)
 def vlc_topk_compact_recent_frac(cache: Cache, scores, k, recent_num, recent_den, k_full, v_full, idx_out) -> None:
     _check(lib.vlc_topk_compact_recent_frac(cache.handle, _ptr(scores), _ptr(k), int(recent_num), int(recent_den),
                                             _ptr(k_full), _ptr(v_full), _ptr(idx_out), _stream()))
+
+
+def vlc_cache_hit_rate(cache: Cache, scores_star, hits_out, rate_out) -> None:
+    _check(lib.vlc_cache_hit_rate(cache.handle, _ptr(scores_star), _ptr(hits_out), _ptr(rate_out), _stream()))
 
 
 def vlc_decode_attn(cache: Cache, layer_begin, layer_end, q, k_new, v_new, sm_scale, out) -> None:

@@ -304,6 +304,16 @@ vlc_status vlc_topk_compact_recent_frac(vlc_cache* cache, const float* scores, c
                                idx_out, stream);
 }
 
+vlc_status vlc_cache_hit_rate(vlc_cache* cache, const float* scores_star, int32_t* hits_out, float* rate_out,
+                              vlc_stream stream) {
+    if (!cache) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_hit_rate: cache is NULL");
+    if (!cache->compacted) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_hit_rate: the cache has not been filled by vlc_topk_compact");
+    if (!scores_star || !hits_out) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_hit_rate: scores_star and hits_out must not be NULL");
+    hipError_t e = vlc::launch_cache_hit_count(*cache, scores_star, hits_out, rate_out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "vlc_cache_hit_rate");
+    return VLC_OK;
+}
+
 vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_end, const void* q,
                            const void* k_new, const void* v_new, const float* sm_scale, void* out,
                            vlc_stream stream) {

@@ -98,6 +98,10 @@ hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const in
                                int32_t n_recent, int32_t recent_num, int32_t recent_den,
                                const void* k_full, const void* v_full, int32_t* idx_out, hipStream_t st);
 
+// |kept positions of the cache ∩ top-k of scores_star| per (b, l, kv head) row, k = the row's budget
+hipError_t launch_cache_hit_count(const vlc_cache& c, const float* scores_star, int32_t* hits_out, float* rate_out,
+                                  hipStream_t st);
+
 // ---- decode ----
 struct DecodeArgs {
     const vlc_cache* c;

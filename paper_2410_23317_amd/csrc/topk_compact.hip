@@ -179,11 +179,16 @@ __device__ __forceinline__ void for_keys(const uint32_t (&key)[NK > 0 ? NK : 1],
 // from memory once for the four digit passes, the count and the ordered emission.
 // The digit histogram is kept in SUB interleaved copies: lane l adds into copy l % SUB, which lies in a
 // bank of its own, so that lanes of a wave with equal digits do not serialise on one LDS word.
-template <int NK>
+// HIT = false: emits the kept positions into the cache (and idx_out).  HIT = true (Def. 3.1): `scores` are the
+// decode-query attention, the top-k set S* is found the same way with the cache's own budget and no
+// recent window, and instead of emitting it the block counts how many positions the cache already holds
+// lie in S*: hits_out[row] = |kept ∩ S*|.
+template <int NK, bool HIT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, CacheDev dev,
                                                              int Hkv, int m, int T_max, int n_recent,
                                                              int recent_num, int recent_den,
-                                                             int32_t* __restrict__ idx_out) {
+                                                             int32_t* __restrict__ idx_out,
+                                                             int32_t* __restrict__ hits_out, float* __restrict__ rate_out) {
     constexpr int kSelSub = NK == 8 ? 4 : 16;                  // short rows: few adds, the clear and the sum dominate
     __shared__ __align__(16) uint32_t hist[256 * kSelSub];
     __shared__ uint32_t sel_bin, sel_above;
@@ -191,9 +196,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     const int row = blockIdx.x;
     const int hkv = row % Hkv, bl = row / Hkv;
     const int kk = dev.kept[bl];
-    if (kk == 0) return;
+    if (kk == 0) {
+        if (HIT && threadIdx.x == 0) {
+            hits_out[row] = 0;
+            if (rate_out) rate_out[row] = 0.f;
+        }
+        return;
+    }
     // forced recent window: a count, or a fraction of this layer's budget (Sec. 5: 10 % of the budget)
-    const int rcnt = recent_den > 0 ? (int)((int64_t)kk * recent_num / recent_den) : min(max(n_recent, 0), kk);
+    const int rcnt = HIT ? 0 : recent_den > 0 ? (int)((int64_t)kk * recent_num / recent_den) : min(max(n_recent, 0), kk);
     const int need = kk - rcnt;                // picked by score among positions [0, mc)
     const int mc = m - rcnt;
     const int cap = kk + T_max;
@@ -299,6 +310,37 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     }
     if (lane == 0) { cnt_gt[wave] = gt; cnt_eq[wave] = eq; }
     __syncthreads();
+    if constexpr (HIT) {
+        // position of the last candidate equal to the k-th key that S* still takes (ties go to the
+        // lower position); then a kept position is a hit if its key is larger, or equal and not beyond it
+        uint32_t eq_run = 0;
+        for (int w = 0; w < wave; ++w) eq_run += cnt_eq[w];
+        const unsigned long long lt_mask = (1ull << lane) - 1ull;
+        for_keys<NK>(key, s, j0, j1, lane, [&](int j, uint32_t u, bool in) {
+            const bool is_eq = in && (u == prefix);
+            const unsigned long long be = __ballot(is_eq);
+            if (is_eq && eq_run + (uint32_t)__popcll(be & lt_mask) == remaining - 1) sel_bin = (uint32_t)j;
+            eq_run += (uint32_t)__popcll(be);
+        });
+        __syncthreads();
+        const int eq_cut = (int)sel_bin;
+        uint32_t hits = 0;
+        for (int r = tid; r < kk; r += kSelThreads) {
+            const int j = out[r];
+            const uint32_t u = order_key(s[j]);
+            hits += (u > prefix || (u == prefix && j <= eq_cut)) ? 1u : 0u;
+        }
+        hits = wave_allreduce_sum_u32(hits);
+        if (lane == 0) cnt_gt[wave] = hits;
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t tot = 0;
+            for (int w = 0; w < kSelWaves; ++w) tot += cnt_gt[w];
+            hits_out[row] = (int32_t)tot;
+            if (rate_out) rate_out[row] = (float)tot / (float)kk;
+        }
+        return;
+    }
     if (need > 0) {
         uint32_t gt_run = 0, eq_run = 0;
         for (int w = 0; w < wave; ++w) { gt_run += cnt_gt[w]; eq_run += cnt_eq[w]; }
@@ -372,7 +414,7 @@ hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const in
                                c.max_items, c.dev);
     // values per lane of a wave's segment (an eighth of the row, rounded up to whole wave loads)
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_SELECT(NK) select_kernel<NK><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, recent_num, recent_den, idx_out)
+#define VLC_SELECT(NK) select_kernel<NK, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr)
     if (per_lane <= 8) VLC_SELECT(8);
     else if (per_lane <= 24) VLC_SELECT(24);
     else if (per_lane <= 64) VLC_SELECT(64);
@@ -386,6 +428,20 @@ hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const in
     if (rowbytes == 128) gather_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
     else if (rowbytes == 256) gather_kernel<256><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
     else gather_kernel<512><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
+    return hipGetLastError();
+}
+
+hipError_t launch_cache_hit_count(const vlc_cache& c, const float* scores_star, int32_t* hits_out, float* rate_out,
+                                  hipStream_t st) {
+    const vlc_shape& s = c.shape;
+    const int rows = s.B * s.L * s.Hkv;
+    const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
+#define VLC_HITS(NK) select_kernel<NK, true><<<rows, kSelThreads, 0, st>>>(scores_star, c.dev, s.Hkv, s.m, c.T_max, 0, 0, 0, nullptr, hits_out, rate_out)
+    if (per_lane <= 8) VLC_HITS(8);
+    else if (per_lane <= 24) VLC_HITS(24);
+    else if (per_lane <= 64) VLC_HITS(64);
+    else VLC_HITS(0);
+#undef VLC_HITS
     return hipGetLastError();
 }
 

@@ -76,6 +76,26 @@ class VLCachePath:
     def status(self) -> None:
         V.vlc_cache_status(self.cache)
 
+    # -- diagnostic (Def. 3.1) ----------------------------------------------------------------
+    def hit_rate(self, q_next, k, sm_scale):
+        """CacheHitRate of the cache against the first decode query q_next [B, L, Hq, d]:
+        returns (hits [B,L,Hkv] int32, rate [B,L,Hkv] float32, scores_star [B,L,Hkv,m])."""
+        s = self.shape
+        if not hasattr(self, "_star"):
+            one = V.make_shape(s.B, s.L, s.Hq, s.Hkv, s.d, s.m, 1, "f32" if s.dtype == V.VLC_F32 else "bf16")
+            dev = self.scores.device
+            self._star = dict(
+                shape=one, scores=torch.empty_like(self.scores),
+                row_max=torch.empty((s.B, s.L, s.Hq, 1), dtype=torch.float32, device=dev),
+                row_sum=torch.empty((s.B, s.L, s.Hq, 1), dtype=torch.float32, device=dev),
+                workspace=torch.empty(V.vlc_workspace_bytes(one), dtype=torch.uint8, device=dev),
+                hits=torch.empty((s.B, s.L, s.Hkv), dtype=torch.int32, device=dev),
+                rate=torch.empty((s.B, s.L, s.Hkv), dtype=torch.float32, device=dev))
+        t = self._star
+        V.vlc_score(t["shape"], q_next, k, sm_scale, self.p, t["scores"], t["row_max"], t["row_sum"], None, t["workspace"])
+        V.vlc_cache_hit_rate(self.cache, t["scores"], t["hits"], t["rate"])
+        return t["hits"], t["rate"], t["scores"]
+
 
 def cache_layer_view(cache: V.Cache, b: int, l: int, appended: int = 0):
     """(Kc, Vc, idx) of request b, layer l as tensors [Hkv, n, d] / [Hkv, n] aliasing the arena,

@@ -89,6 +89,8 @@ def test_cache_bookkeeping_errors(V):
     for num, den in ((1, 0), (-1, 10), (11, 10)):                       # recent fraction outside [0, 1]
         assert V.lib.vlc_topk_compact_recent_frac(h, 1, 1, num, den, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
     assert V.lib.vlc_topk_compact_recent_frac(h, None, 1, 1, 10, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_cache_hit_rate(h, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG        # cache not filled yet
+    assert V.lib.vlc_cache_hit_rate(None, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
     V.lib.vlc_cache_destroy(h)
 
 

@@ -59,6 +59,48 @@ def test_fixed_sliding_window_scoring_policy(w):
     run_and_check(cfg, (1, 10), 2, recent_frac=(1, 10))
 
 
+@pytest.mark.parametrize("kw", [
+    dict(cid=98, dtype="bf16", d=128, Hq=8, Hkv=2, m=1500, tau=24, lead_text=16, n_visual=1460, L=3, B=2, sinks=6),
+    dict(cid=99, dtype="f32", d=64, Hq=4, Hkv=2, m=333, tau=7, lead_text=5, n_visual=320, L=2, B=1, sinks=3),
+])
+def test_cache_hit_rate_against_the_first_decode_query(kw):
+    """Def. 3.1 on the GPU: psi* from the first decode query (the scoring kernels with a one-row
+    window), its TopK with the cache's own budgets, and the intersection with the kept positions."""
+    import paper_2410_23317_amd as V
+    from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
+    from gpu_util import make_shape, upload, decode_upload, assert_close, SCORE_TOL
+    cfg = W.custom_config(name=f"hit{kw['cid']}", alphas=((1, 10),), steps=2, **kw)
+    dev = upload(cfg)
+    path = VLCachePath(make_shape(cfg), alpha=(1, 10), p=0.01, T_max=2)
+    path.compress(dev["q_win"], dev["k"], dev["v"], dev["sm_scale"])
+    path.status()
+    d_dev, d_host = decode_upload(cfg, 0)
+    q_next = d_dev["q"].permute(1, 0, 2, 3).contiguous()                    # [L,B,Hq,d] -> [B,L,Hq,d]
+    hits, rate, star = path.hit_rate(q_next, dev["k"], dev["sm_scale"])
+    torch.cuda.synchronize()
+    hits, rate, star, kk = hits.cpu().numpy(), rate.cpu().numpy(), star.cpu().numpy(), path.k.cpu().numpy()
+    scales = W.sm_scale(cfg)
+    for b in range(cfg.B):
+        for l in range(cfg.L):
+            t = W.layer_inputs(cfg, b, l)
+            want_star = O.decode_query_attention(d_host["q"][l, b], t["k"], scales[l])
+            assert_close(star[b, l], want_star, what=f"psi* b={b} l={l}", **SCORE_TOL)
+            _, _, idx = cache_layer_view(path.cache, b, l)
+            for h in range(cfg.Hkv):
+                k_l = int(kk[b, l])
+                kept = idx[h].cpu().numpy()
+                # integer work on the GPU's own psi* values: bit-exact
+                h_exact, r_exact = O.cache_hit_rate(star[b, l, h].astype(np.float64), kept, k_l)
+                assert hits[b, l, h] == h_exact, (b, l, h, hits[b, l, h], h_exact)
+                assert abs(rate[b, l, h] - r_exact) < 1e-6
+                # against the oracle end to end: may differ only by near-ties at the cut
+                h_o, _ = O.cache_hit_rate(want_star[h], kept, k_l)
+                kth = np.sort(want_star[h])[-k_l]
+                near = int(np.sum(np.abs(want_star[h] - kth) <= 1e-5 * abs(kth)))
+                assert abs(int(hits[b, l, h]) - h_o) <= max(near - 1, 0), (b, l, h, hits[b, l, h], h_o, near)
+    assert 0.0 <= rate.min() and rate.max() <= 1.0
+
+
 def test_cfg1_7b_shape_all_layers():
     cfg = W.CONFIGS[1]
     run_and_check(cfg, cfg.alphas[0], 4)
