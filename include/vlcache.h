@@ -49,7 +49,7 @@ typedef enum { VLC_F32 = 0, VLC_BF16 = 1 } vlc_dtype;
 typedef void* vlc_stream;
 
 /* Problem shape, uniform over the batch (every request has the same m and tau).
- * Supported: d in {64, 128}; Hq % Hkv == 0 with g <= 8; 1 <= tau <= m; g * tau <= 512;
+ * Supported: d in {64, 128}; Hq % Hkv == 0 with g <= 8; 1 <= tau <= min(m, 4096);
  * L <= 1024; B * L <= 2048; dtype is the storage type of Q, K, V and of the decode output. */
 typedef struct {
     int32_t B, L, Hq, Hkv, d, m, tau;

@@ -40,7 +40,7 @@ vlc_status check_shape(const vlc_shape* s) {
     const int g = s->Hq / s->Hkv;
     if (g > 8) return fail(VLC_ERR_SHAPE, "g = Hq/Hkv = %d: at most 8 query heads per KV head", g);
     if (s->tau > s->m) return fail(VLC_ERR_SHAPE, "tau = %d exceeds m = %d", s->tau, s->m);
-    if ((int64_t)g * s->tau > 512) return fail(VLC_ERR_SHAPE, "g * tau = %d exceeds 512 window rows per KV head", g * s->tau);
+    if (s->tau > 4096) return fail(VLC_ERR_SHAPE, "tau = %d exceeds 4096 window rows", s->tau);
     if (s->L > vlc::kMaxLayers) return fail(VLC_ERR_SHAPE, "L = %d exceeds %d", s->L, vlc::kMaxLayers);
     if ((int64_t)s->B * s->L * s->Hq > 65535) return fail(VLC_ERR_SHAPE, "B * L * Hq = %lld exceeds 65535", (long long)s->B * s->L * s->Hq);
     if ((int64_t)s->B * s->L > 2048) return fail(VLC_ERR_SHAPE, "B * L = %lld exceeds 2048", (long long)s->B * s->L);

@@ -81,7 +81,7 @@ struct ScoreArgs {
 size_t score_simple_workspace_bytes(const vlc_shape& s);
 hipError_t launch_rowstats_simple(const ScoreArgs& a);     // fills row_max, row_sum; zeroes nnz if given
 hipError_t launch_colsweep_simple(const ScoreArgs& a);     // scores and/or nnz from row_max,row_sum
-bool score_mfma_supported(const vlc_shape& s);            // bf16, d = 128, g * roundup(tau, 32) <= 512
+bool score_mfma_supported(const vlc_shape& s);            // bf16, d = 128
 size_t score_mfma_workspace_bytes(const vlc_shape& s);
 hipError_t launch_rowstats_mfma(const ScoreArgs& a);       // fills row_max, row_sum, row_max_t; zeroes nnz if given
 hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t);

@@ -36,6 +36,8 @@ struct MfmaArgs {
     unsigned long long* nnz; // may be null
     float log2p;
     int L, Hq, Hkv, g, m, tau, tauP, RP, keys_per_split, nsplit;
+    int rb0;                 // first 32-row block of this launch (a launch covers at most 16 of them)
+    int accumulate;          // sweep 2: add to scores instead of overwriting (row groups after the first)
 };
 
 // Fragment of one operand: lane (l % 32) owns a row (or column) index, lane half l / 32 the
@@ -47,7 +49,7 @@ __device__ __forceinline__ void load_q_frags(const MfmaArgs& a, int bl, int hkv,
     const int half = lane >> 5;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const int r = (wave * RB + rb) * 32 + (lane & 31);
+        const int r = (a.rb0 + wave * RB + rb) * 32 + (lane & 31);
         const int hl = r / a.tauP, iw = r % a.tauP;
         const bool ok = hl < a.g && iw < a.tau;
         const bf16_t* row = a.q_win + (((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0)) * kD;
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
     float m_run[RB], z_run[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const int r = (wave * RB + rb) * 32 + (lane & 31);
+        const int r = (a.rb0 + wave * RB + rb) * 32 + (lane & 31);
         jlim[rb] = a.m - a.tau + (r % a.tauP);
         m_run[rb] = -INFINITY;
         z_run[rb] = 0.f;
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
             load_k_frags(sK, t, lane, kf);
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                if ((wave * RB + rb) * 32 >= a.RP) continue;       // wave-uniform: no rows here
+                if ((a.rb0 + wave * RB + rb) * 32 >= a.RP) continue;       // wave-uniform: no rows here
                 f32x16_t acc = {0};
 #pragma unroll
                 for (int ks = 0; ks < kKSteps; ++ks)
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
         float z = 0.f;
         if (m_run[rb] > -INFINITY) z += z_run[rb] * exp2_fast(m_run[rb] - mm);
         if (mo > -INFINITY) z += zo * exp2_fast(mo - mm);
-        const int r = (wave * RB + rb) * 32 + (lane & 31);
+        const int r = (a.rb0 + wave * RB + rb) * 32 + (lane & 31);
         if (lane < 32 && r < a.RP) a.part[((size_t)group * a.nsplit + split) * a.RP + r] = make_float2(mm, z);
     }
 }
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
         cnt[rb] = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int r = (wave * RB + rb) * 32 + acc_row(i, lane);
+            const int r = (a.rb0 + wave * RB + rb) * 32 + acc_row(i, lane);
             const int hl = r / a.tauP, iw = r % a.tauP;
             const bool ok = hl < a.g && iw < a.tau;
             const size_t o = ((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0);
@@ -251,14 +253,14 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
             float col = 0.f;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                if ((wave * RB + rb) * 32 >= a.RP) continue;
+                if ((a.rb0 + wave * RB + rb) * 32 >= a.RP) continue;
                 f32x16_t acc = {0};
 #pragma unroll
                 for (int ks = 0; ks < kKSteps; ++ks)
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(qf[rb][ks]), as_frag(kf[ks]), acc, 0, 0, 0);
                 // acc[i] = <q_row, k_key>, row = row block base + acc_row(i), key = this lane's
                 if (masked) {
-                    const int base = a.m - a.tau + ((wave * RB + rb) * 32) % a.tauP;
+                    const int base = a.m - a.tau + ((a.rb0 + wave * RB + rb) * 32) % a.tauP;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const bool valid = key <= base + acc_row(i, lane);
@@ -284,13 +286,14 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
             float s = 0.f;
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) s += sCol[w][threadIdx.x];
-            a.scores[(size_t)group * a.m + kc + threadIdx.x] = s;
+            float* dst = a.scores + (size_t)group * a.m + kc + threadIdx.x;
+            *dst = a.accumulate ? *dst + s : s;
         }
     }
     if (a.nnz) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            const int rbase = (wave * RB + rb) * 32;
+            const int rbase = (a.rb0 + wave * RB + rb) * 32;
             if (rbase >= a.RP) continue;
             const uint32_t tot = cnt[rb];                        // already a wave-wide count
             const int hl = rbase / a.tauP;
@@ -300,16 +303,15 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     }
 }
 
-struct Plan { int tauP, RP, waves, rb, nsplit, keys_per_split; };
+struct Plan { int tauP, RP, nsplit, keys_per_split; };
+
+constexpr int kMaxRowBlocksPerLaunch = 16;      // 512 padded window rows per KV head and launch
 
 Plan make_plan(const vlc_shape& s) {
     Plan p;
     const int g = s.Hq / s.Hkv;
     p.tauP = (s.tau + 31) / 32 * 32;
     p.RP = g * p.tauP;
-    if (p.RP <= 128) { p.waves = 4; p.rb = 1; }
-    else if (p.RP <= 256) { p.waves = 8; p.rb = 1; }      // one row block per wave keeps the sweeps at 8 waves per CU
-    else { p.waves = 16; p.rb = 1; }
     const int groups = s.B * s.L * s.Hkv;
     const int chunks = (s.m + kChunk - 1) / kChunk;
     // Splits of the key range per KV group.  Measured on the 7B and 34B shapes: about one resident
@@ -336,6 +338,7 @@ MfmaArgs make_args(const ScoreArgs& a, const Plan& p) {
     m.log2p = log2f(a.p);
     m.L = s.L; m.Hq = s.Hq; m.Hkv = s.Hkv; m.g = s.Hq / s.Hkv; m.m = s.m; m.tau = s.tau;
     m.tauP = p.tauP; m.RP = p.RP; m.keys_per_split = p.keys_per_split; m.nsplit = p.nsplit;
+    m.rb0 = 0; m.accumulate = 0;
     return m;
 }
 
@@ -346,9 +349,7 @@ size_t part_bytes(const vlc_shape& s, const Plan& p) {
 }  // namespace
 
 bool score_mfma_supported(const vlc_shape& s) {
-    if (s.dtype != VLC_BF16 || s.d != kD) return false;
-    const int g = s.Hq / s.Hkv;
-    return g * ((s.tau + 31) / 32 * 32) <= 512;
+    return s.dtype == VLC_BF16 && s.d == kD;
 }
 
 size_t score_mfma_workspace_bytes(const vlc_shape& s) {
@@ -356,15 +357,23 @@ size_t score_mfma_workspace_bytes(const vlc_shape& s) {
     return part_bytes(s, make_plan(s));
 }
 
+// A launch covers up to 16 row blocks (32 padded window rows each) of every KV group; longer windows
+// take several launches over consecutive row-block ranges.  Block shape by row blocks in the launch:
+// up to 4 -> 4 waves, up to 8 -> 8 waves, else 8 waves x 2 row blocks (sweep 1) or 16 waves (sweep 2).
 hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
     const vlc_shape& s = a.s;
     const Plan p = make_plan(s);
     MfmaArgs m = make_args(a, p);
     const int groups = s.B * s.L * s.Hkv;
     dim3 grid(p.nsplit, groups);
-    if (p.waves == 4) rowstats_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
-    else if (p.waves == 8) rowstats_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
-    else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);        // measured faster than 16 x 1 for this sweep
+    const int total_rb = p.RP / 32;
+    for (int rb0 = 0; rb0 < total_rb; rb0 += kMaxRowBlocksPerLaunch) {
+        const int nrb = total_rb - rb0 < kMaxRowBlocksPerLaunch ? total_rb - rb0 : kMaxRowBlocksPerLaunch;
+        m.rb0 = rb0;
+        if (nrb <= 4) rowstats_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
+        else if (nrb <= 8) rowstats_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
+        else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);        // measured faster than 16 x 1 for this sweep
+    }
     const size_t n = (size_t)groups * p.RP;
     rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
         m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv,
@@ -378,9 +387,15 @@ hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t) {
     MfmaArgs m = make_args(a, p);
     if (have_row_max_t) m.row_max_t = a.row_max_t;
     dim3 grid(p.nsplit, s.B * s.L * s.Hkv);
-    if (p.waves == 4) colsweep_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
-    else if (p.waves == 8) colsweep_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
-    else colsweep_mfma_kernel<16, 1><<<grid, 1024, 0, a.stream>>>(m);
+    const int total_rb = p.RP / 32;
+    for (int rb0 = 0; rb0 < total_rb; rb0 += kMaxRowBlocksPerLaunch) {
+        const int nrb = total_rb - rb0 < kMaxRowBlocksPerLaunch ? total_rb - rb0 : kMaxRowBlocksPerLaunch;
+        m.rb0 = rb0;
+        m.accumulate = rb0 > 0;                 // launches of one stream run in order: the column sums add up deterministically
+        if (nrb <= 4) colsweep_mfma_kernel<4, 1><<<grid, 256, 0, a.stream>>>(m);
+        else if (nrb <= 8) colsweep_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
+        else colsweep_mfma_kernel<16, 1><<<grid, 1024, 0, a.stream>>>(m);
+    }
     return hipGetLastError();
 }
 

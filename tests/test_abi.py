@@ -44,7 +44,7 @@ def test_shape_validation(V):
     bad = [
         (dict(Hq=4, Hkv=3), V.VLC_ERR_SHAPE), (dict(d=96), V.VLC_ERR_SHAPE), (dict(Hq=18, Hkv=2), V.VLC_ERR_SHAPE),
         (dict(tau=600, m=512), V.VLC_ERR_SHAPE), (dict(tau=0), V.VLC_ERR_SHAPE), (dict(L=0), V.VLC_ERR_SHAPE),
-        (dict(Hq=8, Hkv=1, tau=128), V.VLC_ERR_SHAPE), (dict(dtype=7), V.VLC_ERR_DTYPE),
+        (dict(tau=4097, m=5000), V.VLC_ERR_SHAPE), (dict(dtype=7), V.VLC_ERR_DTYPE),
     ]
     base = dict(B=1, L=2, Hq=4, Hkv=2, d=64, m=512, tau=32, dtype=V.VLC_F32)
     for kw, code in bad:

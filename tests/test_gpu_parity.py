@@ -101,6 +101,22 @@ def test_cache_hit_rate_against_the_first_decode_query(kw):
     assert 0.0 <= rate.min() and rate.max() <= 1.0
 
 
+@pytest.mark.parametrize("kw", [
+    # g * padded tau = 4 * 224 = 896 window rows per KV head: two launches of 16 + 12 row blocks
+    dict(cid=100, dtype="bf16", d=128, Hq=8, Hkv=2, m=1100, tau=200, lead_text=20, n_visual=1000, L=2, B=1, sinks=4),
+    # g = 7 with a padded window of 128: 28 row blocks, the second launch with 12
+    dict(cid=101, dtype="bf16", d=128, Hq=7, Hkv=1, m=900, tau=100, lead_text=10, n_visual=800, L=2, B=2, sinks=4),
+    # 17 row blocks: a second launch with a single row block (the 4-wave kernels with three idle waves)
+    dict(cid=102, dtype="bf16", d=128, Hq=1, Hkv=1, m=700, tau=530, lead_text=10, n_visual=100, L=1, B=1, sinks=2),
+])
+def test_windows_longer_than_one_launch_of_row_blocks(kw):
+    """Post-vision windows of a few hundred tokens (App. A.3 notes the cost grows with tau): the
+    matrix-core sweeps take several launches over consecutive row-block ranges, column sums
+    accumulate across them."""
+    cfg = W.custom_config(name=f"long-window{kw['cid']}", alphas=((1, 5),), steps=2, **kw)
+    run_and_check(cfg, (1, 5), 2)
+
+
 def test_cfg1_7b_shape_all_layers():
     cfg = W.CONFIGS[1]
     run_and_check(cfg, cfg.alphas[0], 4)
