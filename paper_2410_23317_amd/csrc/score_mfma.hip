@@ -100,7 +100,7 @@ __global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
     __shared__ __align__(16) bf16_t sK[kChunk * kPitch];
     const int group = blockIdx.y, split = blockIdx.x;
     const int hkv = group % a.Hkv, bl = group / a.Hkv, l = bl % a.L;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;     // wave index in a scalar register
     const float c = (a.sm_scale ? a.sm_scale[l] : rsqrtf((float)kD)) * kLog2e;
     const bf16_t* kg = a.k + (size_t)group * a.m * kD;
     const int k_begin = split * a.keys_per_split;
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     __shared__ float sCol[WAVES][kChunk];
     const int group = blockIdx.y, split = blockIdx.x;
     const int hkv = group % a.Hkv, bl = group / a.Hkv, l = bl % a.L;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;     // wave index in a scalar register
     const float c = (a.sm_scale ? a.sm_scale[l] : rsqrtf((float)kD)) * kLog2e;
     const bf16_t* kg = a.k + (size_t)group * a.m * kD;
     const int k_begin = split * a.keys_per_split;
