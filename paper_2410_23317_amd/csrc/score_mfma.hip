@@ -95,7 +95,7 @@ __device__ __forceinline__ int acc_row(int i, int lane) { return 8 * (i >> 2) + 
 // ------------------------------------------------------------------------------------------------
 // Sweep 1: partial row statistics of one key range of one KV group.
 template <int WAVES, int RB>
-__global__ __launch_bounds__(WAVES * 64) void rowstats_mfma_kernel(MfmaArgs a) {
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 0) void rowstats_mfma_kernel(MfmaArgs a) {   // 4-wave blocks: registers for 3 blocks per CU, accumulators stay out of the AGPRs
     constexpr int THREADS = WAVES * 64;
     __shared__ __align__(16) bf16_t sK[kChunk * kPitch];
     const int group = blockIdx.y, split = blockIdx.x;
