@@ -5,6 +5,8 @@ resident in HBM: compression (vlc_score -> vlc_sparsity -> vlc_allocate -> vlc_t
 T decode steps of vlc_decode_attn, each one ragged launch over all layers.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--no-cpu]
+  python bench.py --paper-grid     the (batch, prompt length) grid of the paper's speed benchmark instead:
+                                   one JSON line per grid point, compression and decode time on random inputs
 """
 from __future__ import annotations
 
@@ -40,10 +42,15 @@ def main() -> int:
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--paper-grid", action="store_true",
+                    help="run the (batch, prompt length) grid of the paper's speed benchmark (App. A.4) instead")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
+
+    if args.paper_grid:
+        return paper_grid(args)
 
     import numpy as np
     import torch
@@ -189,6 +196,73 @@ def main() -> int:
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, alpha, args.cpu_seconds)
     print(json.dumps(result))
+    return 0
+
+
+# Compression overhead the paper reports (App. A.4, ms per batch, 8x A100 40 GB node, Triton kernels, model and
+# precision not stated; scoring window = last 50 tokens, cache compressed to 10 %): context, not a target.
+PAPER_COMPRESS_MS = {
+    1: {1: 5.2, 2: 7.2, 4: 10.1, 8: 17.3, 16: 28.3, 32: 49.7, 64: 100.2, 128: 189.6},
+    2: {1: 6.4, 2: 9.5, 4: 15.8, 8: 29.0, 16: 51.8, 32: 92.5, 64: 188.5},
+    4: {1: 8.5, 2: 15.2, 4: 27.4, 8: 52.5, 16: 93.3, 32: 175.8},
+    8: {1: 13.7, 2: 26.8, 4: 50.9, 8: 96.6, 16: 178.4},
+    16: {1: 25.2, 2: 51.3, 4: 95.6, 8: 183.5},
+    32: {1: 48.5, 2: 97.1, 4: 182.6},
+    64: {1: 91.6, 2: 186.7},
+}
+
+
+def paper_grid(args) -> int:
+    """The paper's speed-benchmark grid on the 7B shape (32 layers, 32 query / 8 KV heads, d = 128, bf16): prompt
+    lengths 1K..128K, batch 1..64, window of the last 50 tokens, 10 % budget.  Inputs are unit-normal random
+    tensors made on the device (shapes only; no sinks, no temperature), so budgets come out nearly equal."""
+    import numpy as np
+    import torch
+
+    import paper_2410_23317_amd as V
+    from paper_2410_23317_amd.pipeline import VLCachePath
+
+    torch.cuda.set_device(0)
+    L, Hq, Hkv, d, tau, T = 32, 32, 8, 128, 50, 20
+    dt = torch.bfloat16
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for B, row in PAPER_COMPRESS_MS.items():
+        for kilo, paper_ms in row.items():
+            m = kilo * 1024
+            q = torch.randn((B, L, Hq, tau, d), device="cuda").to(dt)
+            k = torch.randn((B, L, Hkv, m, d), device="cuda", dtype=dt)
+            v = torch.randn((B, L, Hkv, m, d), device="cuda", dtype=dt)
+            sm = torch.full((L,), 1.0 / np.sqrt(d), device="cuda")
+            path = VLCachePath(V.make_shape(B, L, Hq, Hkv, d, m, tau, "bf16"), alpha=(1, 10), T_max=T)
+            for _ in range(2):
+                path.compress(q, k, v, sm)
+            path.status()
+            ev[0].record()
+            for _ in range(3):
+                path.compress(q, k, v, sm)
+            ev[1].record()
+            torch.cuda.synchronize()
+            comp_ms = ev[0].elapsed_time(ev[1]) / 3
+            dq = torch.randn((T, L, B, Hq, d), device="cuda").to(dt)
+            dk = torch.randn((T, L, B, Hkv, d), device="cuda").to(dt)
+            dv = torch.randn_like(dk)
+            out = torch.empty((T, L, B, Hq, d), device="cuda", dtype=dt)
+            path.decode_steps(0, L, T, dq, dk, dv, sm, out)
+            path.compress(q, k, v, sm)
+            ev[0].record()
+            path.decode_steps(0, L, T, dq, dk, dv, sm, out)
+            ev[1].record()
+            torch.cuda.synchronize()
+            dec_us = ev[0].elapsed_time(ev[1]) * 1e3 / T
+            kk = path.k.cpu().numpy().astype(np.int64)
+            kv_bytes = 2.0 * Hkv * d * 2 * (kk.sum() + B * L * (T + 1) / 2.0)
+            print(json.dumps({"batch": B, "prompt_tokens": m, "compress_ms_per_batch": round(comp_ms, 3),
+                              "paper_compress_ms_per_batch_a100": paper_ms,
+                              "decode_us_per_all_layer_launch": round(dec_us, 1),
+                              "decode_us_per_layer_step": round(dec_us / L, 3),
+                              "decode_gb_per_s": round(kv_bytes / dec_us / 1e3, 0)}), flush=True)
+            del path, q, k, v, dq, dk, dv, out
+            torch.cuda.empty_cache()
     return 0
 
 

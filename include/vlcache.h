@@ -50,7 +50,7 @@ typedef void* vlc_stream;
 
 /* Problem shape, uniform over the batch (every request has the same m and tau).
  * Supported: d in {64, 128}; Hq % Hkv == 0 with g <= 8; 1 <= tau <= min(m, 4096);
- * L <= 1024; B * L <= 2048; dtype is the storage type of Q, K, V and of the decode output. */
+ * L <= 1024; B * L <= 2048; B * L * Hkv <= 65535; dtype is the storage type of Q, K, V and of the decode output. */
 typedef struct {
     int32_t B, L, Hq, Hkv, d, m, tau;
     int32_t dtype;             /* vlc_dtype */

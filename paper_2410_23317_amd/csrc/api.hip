@@ -42,7 +42,8 @@ vlc_status check_shape(const vlc_shape* s) {
     if (s->tau > s->m) return fail(VLC_ERR_SHAPE, "tau = %d exceeds m = %d", s->tau, s->m);
     if (s->tau > 4096) return fail(VLC_ERR_SHAPE, "tau = %d exceeds 4096 window rows", s->tau);
     if (s->L > vlc::kMaxLayers) return fail(VLC_ERR_SHAPE, "L = %d exceeds %d", s->L, vlc::kMaxLayers);
-    if ((int64_t)s->B * s->L * s->Hq > 65535) return fail(VLC_ERR_SHAPE, "B * L * Hq = %lld exceeds 65535", (long long)s->B * s->L * s->Hq);
+    if ((int64_t)s->B * s->L * s->Hkv > 65535) return fail(VLC_ERR_SHAPE, "B * L * Hkv = %lld exceeds 65535", (long long)s->B * s->L * s->Hkv);
+    if ((double)s->B * s->L * s->Hq * ((s->m + 255) / 256) > 2.0e9) return fail(VLC_ERR_SHAPE, "B * L * Hq * m exceeds the grid of the scoring sweeps");
     if ((int64_t)s->B * s->L > 2048) return fail(VLC_ERR_SHAPE, "B * L = %lld exceeds 2048", (long long)s->B * s->L);
     if ((double)s->m * s->d * s->Hkv * s->L * s->B > 4.0e12) return fail(VLC_ERR_SHAPE, "K tensor larger than 4e12 elements");
     return VLC_OK;

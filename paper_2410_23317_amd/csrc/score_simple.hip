@@ -54,11 +54,11 @@ __global__ __launch_bounds__(256) void rowstats_simple_kernel(
     const T* __restrict__ q_win, const T* __restrict__ k, const float* __restrict__ sm_scale,
     float2* __restrict__ part, int L, int Hq, int Hkv, int m, int tau, int nchunks) {
     __shared__ __align__(16) float qs[kRT * D];
-    __shared__ float2 red[512][4];
-    const int r = blockIdx.y;                       // (b*L + l)*Hq + h
+    __shared__ float2 red[kRT][4];
+    const int r = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;      // r = (b*L + l)*Hq + h; 1-D grid: rows * chunks
     const int h = r % Hq, bl = r / Hq, l = bl % L;
     const int g = Hq / Hkv;
-    const int j = blockIdx.x * kScoreChunk + threadIdx.x;
+    const int j = chunk * kScoreChunk + threadIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const float scale = sm_scale ? sm_scale[l] : rsqrtf((float)D);
     const T* krow = k + (((size_t)bl * Hkv + h / g) * m + (j < m ? j : 0)) * D;
@@ -77,19 +77,20 @@ __global__ __launch_bounds__(256) void rowstats_simple_kernel(
             const float wmax = wave_allreduce_max(valid ? s : -INFINITY);
             const float e = valid ? exp2_fast((s - wmax) * kLog2e) : 0.f;
             const float wsum = wave_allreduce_sum(e);
-            if (lane == 0) red[i][wave] = make_float2(wmax, wsum);
+            if (lane == 0) red[ii][wave] = make_float2(wmax, wsum);
         }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < tau; i += blockDim.x) {
-        float M = -INFINITY;
+        __syncthreads();
+        if (threadIdx.x < n) {                       // combine the four waves for the rows of this stage
+            const int ii = threadIdx.x;
+            float M = -INFINITY;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) M = fmaxf(M, red[i][w].x);
-        float Z = 0.f;
+            for (int w = 0; w < 4; ++w) M = fmaxf(M, red[ii][w].x);
+            float Z = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-            if (red[i][w].x > -INFINITY) Z += red[i][w].y * exp2_fast((red[i][w].x - M) * kLog2e);
-        part[((size_t)r * tau + i) * nchunks + blockIdx.x] = make_float2(M, Z);
+            for (int w = 0; w < 4; ++w)
+                if (red[ii][w].x > -INFINITY) Z += red[ii][w].y * exp2_fast((red[ii][w].x - M) * kLog2e);
+            part[((size_t)r * tau + i0 + ii) * nchunks + chunk] = make_float2(M, Z);
+        }
     }
 }
 
@@ -121,10 +122,11 @@ __global__ __launch_bounds__(256) void colsweep_simple_kernel(
     int L, int Hq, int Hkv, int m, int tau) {
     __shared__ __align__(16) float qs[kRT * D];
     __shared__ float ms[kRT], izs[kRT];
-    const int rk = blockIdx.y;                      // (b*L + l)*Hkv + hkv
+    const int nchunks = (m + kScoreChunk - 1) / kScoreChunk;
+    const int rk = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;     // rk = (b*L + l)*Hkv + hkv
     const int hkv = rk % Hkv, bl = rk / Hkv, l = bl % L;
     const int g = Hq / Hkv;
-    const int j = blockIdx.x * kScoreChunk + threadIdx.x;
+    const int j = chunk * kScoreChunk + threadIdx.x;
     const int lane = threadIdx.x & 63;
     const float scale = sm_scale ? sm_scale[l] : rsqrtf((float)D);
     const T* krow = k + ((size_t)rk * m + (j < m ? j : 0)) * D;
@@ -179,7 +181,7 @@ hipError_t rowstats_impl(const ScoreArgs& a) {
     const vlc_shape& s = a.s;
     const int nchunks = (s.m + kScoreChunk - 1) / kScoreChunk;
     const size_t rows = (size_t)s.B * s.L * s.Hq * s.tau;
-    dim3 grid(nchunks, s.B * s.L * s.Hq);
+    const unsigned grid = (unsigned)nchunks * (unsigned)(s.B * s.L * s.Hq);
     rowstats_simple_kernel<T, D><<<grid, 256, 0, a.stream>>>(
         (const T*)a.q_win, (const T*)a.k, a.sm_scale, (float2*)a.workspace, s.L, s.Hq, s.Hkv, s.m, s.tau, nchunks);
     rowstats_merge_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, a.stream>>>(
@@ -192,7 +194,7 @@ template <typename T, int D>
 hipError_t colsweep_impl(const ScoreArgs& a) {
     const vlc_shape& s = a.s;
     const int nchunks = (s.m + kScoreChunk - 1) / kScoreChunk;
-    dim3 grid(nchunks, s.B * s.L * s.Hkv);
+    const unsigned grid = (unsigned)nchunks * (unsigned)(s.B * s.L * s.Hkv);
     colsweep_simple_kernel<T, D><<<grid, 256, 0, a.stream>>>(
         (const T*)a.q_win, (const T*)a.k, a.sm_scale, a.row_max, a.row_sum, a.scores,
         (unsigned long long*)a.nnz, logf(a.p), s.L, s.Hq, s.Hkv, s.m, s.tau);

@@ -108,6 +108,8 @@ def test_cache_hit_rate_against_the_first_decode_query(kw):
     dict(cid=101, dtype="bf16", d=128, Hq=7, Hkv=1, m=900, tau=100, lead_text=10, n_visual=800, L=2, B=2, sinks=4),
     # 17 row blocks: a second launch with a single row block (the 4-wave kernels with three idle waves)
     dict(cid=102, dtype="bf16", d=128, Hq=1, Hkv=1, m=700, tau=530, lead_text=10, n_visual=100, L=1, B=1, sinks=2),
+    # fp32 storage takes the plain-ALU sweeps, which stage 32 window rows at a time: 19 stages
+    dict(cid=103, dtype="f32", d=64, Hq=2, Hkv=1, m=800, tau=600, lead_text=10, n_visual=100, L=1, B=2, sinks=2),
 ])
 def test_windows_longer_than_one_launch_of_row_blocks(kw):
     """Post-vision windows of a few hundred tokens (App. A.3 notes the cost grows with tau): the
