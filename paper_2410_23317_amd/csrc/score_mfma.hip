@@ -65,6 +65,12 @@ struct KStage {
     static constexpr int N = kChunk * (kD / 8) / THREADS;      // 16-byte pieces per thread
     uint4 r[N];
     __device__ __forceinline__ void load(const bf16_t* kg, int key0, int m) {
+        if (key0 + kChunk <= m) {               // block-uniform: a whole chunk needs no per-row test
+            const uint4* src = reinterpret_cast<const uint4*>(kg + (size_t)key0 * kD) + threadIdx.x;
+#pragma unroll
+            for (int u = 0; u < N; ++u) r[u] = src[THREADS * u];
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < N; ++u) {
             const int x = threadIdx.x + THREADS * u;
