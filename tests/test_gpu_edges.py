@@ -292,6 +292,46 @@ def test_compression_is_deterministic_and_steps_entry_point_matches_single_steps
         assert torch.equal(a, b)
 
 
+def test_whole_path_replays_from_a_hip_graph():
+    """Callers may record the path into a HIP graph (nothing in it allocates, synchronises or uses a
+    memset node): every replay, with eager work and synchronisations in between, equals the eager run."""
+    V = _V()
+    from gpu_util import make_shape, upload
+    from paper_2410_23317_amd.pipeline import VLCachePath
+    cfg = _small_cfg(cid=86, m=1500, n_visual=1400)                 # rows of several 256-slot units: merges replay too
+    dev = upload(cfg)
+    T = 3
+    steps = [W.decode_step_inputs(cfg, t) for t in range(T)]
+    stack = {n: torch.from_numpy(np.stack([s[n] for s in steps])).to(torch.bfloat16).cuda() for n in ("q", "k_new", "v_new")}
+
+    def run(path, out):
+        path.compress(dev["q_win"], dev["k"], dev["v"], dev["sm_scale"])
+        for t in range(T):
+            path.decode(0, cfg.L, stack["q"][t], stack["k_new"][t], stack["v_new"][t], dev["sm_scale"], out[t])
+
+    eager = VLCachePath(make_shape(cfg), alpha=(1, 2), T_max=T, want_idx=True)
+    out_e = torch.empty((T, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=torch.bfloat16, device="cuda")
+    run(eager, out_e)
+    eager.status()
+    path = VLCachePath(make_shape(cfg), alpha=(1, 2), T_max=T, want_idx=True)
+    out_g = torch.zeros_like(out_e)
+    run(path, out_g)                                                # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(path, out_g)
+    for rep in range(3):
+        out_g.zero_()
+        path.scores.zero_(); path.k.zero_(); path.idx_out.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        path.status()
+        assert torch.equal(path.scores, eager.scores) and torch.equal(path.k, eager.k), rep
+        assert torch.equal(path.idx_out, eager.idx_out) and torch.equal(path.nnz, eager.nnz), rep
+        assert torch.equal(out_g, out_e), rep
+
+
 @pytest.mark.parametrize("env", [{"VLC_UNIT_SLOTS": "128"}, {"VLC_UNIT_SLOTS": "128", "VLC_DECODE_MERGE": "2"},
                                  {"VLC_UNIT_SLOTS": "256"}, {"VLC_UNIT_SLOTS": "128", "VLC_DECODE_ORDER": "2"},
                                  {"VLC_UNIT_SLOTS": "256", "VLC_DECODE_ORDER": "2", "VLC_DECODE_MERGE": "2"}])
