@@ -37,6 +37,31 @@ def test_ragged_small_shapes(kw):
     run_and_check(cfg, (1, 5), 5)
 
 
+def _random_shapes(n, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        g = int(r.integers(1, 9))                       # every group size the decode kernel is instantiated for
+        Hkv = int(r.integers(1, 4))
+        d = int(r.choice([64, 128]))
+        dtype = str(r.choice(["bf16", "bf16", "f32"]))
+        m = int(r.integers(80, 1400))
+        tau = int(r.integers(1, min(m // 2, 90)))
+        lead = int(r.integers(0, 10))
+        nvis = int(r.integers(m // 2, m - tau - lead)) if m - tau - lead > m // 2 else m // 2
+        out.append(dict(cid=200 + i, dtype=dtype, d=d, Hq=g * Hkv, Hkv=Hkv, m=m, tau=tau, lead_text=lead, n_visual=nvis,
+                        L=int(r.integers(1, 5)), B=int(r.integers(1, 4)), sinks=int(r.integers(0, 6))))
+    return out
+
+
+@pytest.mark.parametrize("kw", _random_shapes(14, seed=20241023), ids=lambda kw: f"g{kw['Hq'] // kw['Hkv']}-d{kw['d']}-{kw['dtype']}-m{kw['m']}-tau{kw['tau']}")
+def test_seeded_random_shapes(kw):
+    """A fixed draw of small shapes over every group size 1..8, both head dimensions and storage types,
+    window and prompt lengths that are not multiples of any tile size."""
+    cfg = W.custom_config(name=f"rand{kw['cid']}", alphas=((1, 4),), steps=3, **kw)
+    run_and_check(cfg, (1, 4), 3)
+
+
 def test_recent_window_variant():
     cfg = W.custom_config(cid=95, name="recent", dtype="bf16", d=128, Hq=8, Hkv=2, m=400, tau=16, lead_text=8,
                           n_visual=360, L=2, B=1, sinks=4, alphas=((1, 5),))
