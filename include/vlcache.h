@@ -48,12 +48,24 @@ typedef enum { VLC_F32 = 0, VLC_BF16 = 1 } vlc_dtype;
  * NULL is the device's default stream. */
 typedef void* vlc_stream;
 
-/* Problem shape, uniform over the batch (every request has the same m and tau).
+/* Problem shape.  m and tau are the prompt length and the post-vision window length (paper Sec. 3.2),
+ * and the strides of every tensor: K, V [B,L,Hkv,m,d], Q' [B,L,Hq,tau,d], scores [B,L,Hkv,m], ...
  * Supported: d in {64, 128}; Hq % Hkv == 0 with g <= 8; 1 <= tau <= min(m, 4096);
- * L <= 1024; B * L <= 2048; B * L * Hkv <= 65535; dtype is the storage type of Q, K, V and of the decode output. */
+ * L <= 1024; B * L <= 2048; B * L * Hkv <= 65535; dtype is the storage type of Q, K, V and of the decode output.
+ *
+ * lens == NULL: every request has prompt length m and window tau.
+ * lens != NULL (ragged batch): DEVICE array int32 [B][2] = (m_b, tau_b) with 1 <= tau_b <= tau,
+ * tau_b <= m_b <= m.  Request b then uses keys [0, m_b) of its K/V rows and rows [0, tau_b) of its
+ * window (row i is prompt position m_b - tau_b + i); the rest of the padded tensors is never read.
+ * Outputs beyond a request's lengths: scores[b,..,j >= m_b] = 0; row_max / row_sum rows >= tau_b are
+ * left untouched; budgets are computed from m_b (total floor(alpha L m_b), clips ceil(m_b/100) and m_b).
+ * The array is read when a call's kernels run (it must stay valid until then); values outside
+ * the ranges above are clamped into them by the scoring calls and reported as VLC_ERR_INVALID_ARG by
+ * vlc_cache_status after vlc_topk_compact, which also copies the array into the cache. */
 typedef struct {
     int32_t B, L, Hq, Hkv, d, m, tau;
     int32_t dtype;             /* vlc_dtype */
+    const int32_t* lens;       /* device, [B][2], or NULL */
 } vlc_shape;
 
 const char* vlc_last_error_string(void);

@@ -29,7 +29,7 @@ class VlcError(RuntimeError):
 
 
 class vlc_shape(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("B", "L", "Hq", "Hkv", "d", "m", "tau", "dtype")]
+    _fields_ = [(n, C.c_int32) for n in ("B", "L", "Hq", "Hkv", "d", "m", "tau", "dtype")] + [("lens", C.c_void_p)]
 
 
 class vlc_cache_layout(C.Structure):
@@ -98,9 +98,12 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def make_shape(B, L, Hq, Hkv, d, m, tau, dtype) -> vlc_shape:
+def make_shape(B, L, Hq, Hkv, d, m, tau, dtype, lens=None) -> vlc_shape:
+    """lens: optional int32 device tensor [B, 2] of per-request (m_b, tau_b); the caller keeps it alive."""
     code = {torch.float32: VLC_F32, torch.bfloat16: VLC_BF16, "f32": VLC_F32, "bf16": VLC_BF16}.get(dtype, dtype)
-    return vlc_shape(B, L, Hq, Hkv, d, m, tau, code)
+    if lens is not None:
+        assert lens.dtype == torch.int32 and lens.is_cuda and lens.is_contiguous() and tuple(lens.shape) == (B, 2)
+    return vlc_shape(B, L, Hq, Hkv, d, m, tau, code, None if lens is None else lens.data_ptr())
 
 
 def vlc_version() -> str:

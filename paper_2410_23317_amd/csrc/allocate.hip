@@ -9,8 +9,9 @@ namespace vlc {
 namespace {
 
 // One block per request; thread t owns layers t, t + blockDim, ...  (L <= kMaxLayers).
-__global__ __launch_bounds__(256) void allocate_kernel(const uint64_t* __restrict__ nnz, int L, int Hq, int m,
-                                                       uint64_t B_tot, int32_t* __restrict__ k_out,
+__global__ __launch_bounds__(256) void allocate_kernel(const uint64_t* __restrict__ nnz, int L, int Hq, int m_max, int tau,
+                                                       uint64_t alpha_num, uint64_t alpha_den,
+                                                       const int32_t* __restrict__ lens, int32_t* __restrict__ k_out,
                                                        float* __restrict__ beta_out) {
     __shared__ uint64_t n_l[kMaxLayers];
     __shared__ uint64_t rem[kMaxLayers];
@@ -18,6 +19,8 @@ __global__ __launch_bounds__(256) void allocate_kernel(const uint64_t* __restric
     __shared__ uint64_t red[256];
     const int b = blockIdx.x;
     const int t = threadIdx.x;
+    const int m = request_len(lens, b, m_max, tau).m;                       // this request's prompt length
+    const uint64_t B_tot = alpha_num * (uint64_t)L * (uint64_t)m / alpha_den;   // floor(alpha L m) tokens for the request
     uint64_t local = 0;
     for (int l = t; l < L; l += blockDim.x) {
         uint64_t s = 0;
@@ -65,9 +68,10 @@ __global__ __launch_bounds__(256) void allocate_kernel(const uint64_t* __restric
 
 }  // namespace
 
-hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t B_tot, int32_t* k_out,
+hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t alpha_num, int64_t alpha_den, int32_t* k_out,
                            float* beta_out, hipStream_t st) {
-    allocate_kernel<<<s.B, 256, 0, st>>>(nnz, s.L, s.Hq, s.m, (uint64_t)B_tot, k_out, beta_out);
+    allocate_kernel<<<s.B, 256, 0, st>>>(nnz, s.L, s.Hq, s.m, s.tau, (uint64_t)alpha_num, (uint64_t)alpha_den, s.lens,
+                                         k_out, beta_out);
     return hipGetLastError();
 }
 

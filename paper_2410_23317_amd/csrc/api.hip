@@ -163,14 +163,14 @@ vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alp
     // n_l * B_tot must fit 64 bits: n_l <= Hq * region size
     if ((double)shape->Hq * region_size(*shape) * (double)B_tot > 1.8e19)
         return fail(VLC_ERR_SHAPE, "vlc_allocate: Hq * region * budget exceeds 64-bit arithmetic");
-    hipError_t e = vlc::launch_allocate(*shape, nnz, B_tot, k_out, beta_out, (hipStream_t)stream);
+    hipError_t e = vlc::launch_allocate(*shape, nnz, alpha_num, alpha_den, k_out, beta_out, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "vlc_allocate");
     return VLC_OK;
 }
 
 struct ArenaPlan {
     vlc_cache_layout lay;
-    size_t items_off, items2_off, layer_start_off, row_first_off, partials_off, counters_off;
+    size_t items_off, items2_off, layer_start_off, row_first_off, partials_off, counters_off, lens_off;
     int32_t unit_slots;
     int64_t max_items;
 };
@@ -206,6 +206,7 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     plan->row_first_off = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
     plan->partials_off = off;     off = align_up(off + (size_t)plan->max_items * g * (s->d + 2) * sizeof(float), 256);
     plan->counters_off = off;     off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
+    plan->lens_off = off;         off = align_up(off + (size_t)s->B * 2 * sizeof(int32_t), 256);
     lay->total_bytes = off;
     lay->slots_per_request = spr;
     return VLC_OK;
@@ -250,6 +251,8 @@ vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k
     c->dev.row_item_first = (int32_t*)(c->arena + plan.row_first_off);
     c->dev.partials = (float*)(c->arena + plan.partials_off);
     c->dev.counters = (int32_t*)(c->arena + plan.counters_off);
+    c->dev.lens = (int32_t*)(c->arena + plan.lens_off);
+    c->ragged = false;
     c->compacted = false;
     *out = c;
     return VLC_OK;
@@ -270,38 +273,43 @@ vlc_status vlc_cache_status(vlc_cache* cache, vlc_stream stream) {
     hipError_t e = hipMemcpyAsync(st, cache->dev.status, sizeof(st), hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "vlc_cache_status");
+    if (st[0] == VLC_ERR_INVALID_ARG && st[2] == -2)
+        return fail(VLC_ERR_INVALID_ARG, "request %d: per-request lengths (m_b = %d) are outside 1 <= tau_b <= min(tau, m_b), m_b <= m", st[1], st[3]);
     if (st[0] == VLC_ERR_INVALID_ARG) return fail(VLC_ERR_INVALID_ARG, "budget k[%d][%d] = %d is outside [1, m]", st[1], st[2], st[3]);
     if (st[0] == VLC_ERR_CAPACITY) return fail(VLC_ERR_CAPACITY, "request %d: budgets plus reserved appends need %d slots, arena has %lld",
                                                st[1], st[3], (long long)cache->slots_per_request);
     return (vlc_status)st[0];
 }
 
-static vlc_status topk_compact_common(const char* who, vlc_cache* cache, const float* scores, const int32_t* k,
+static vlc_status topk_compact_common(const char* who, vlc_cache* cache, const int32_t* lens, const float* scores, const int32_t* k,
                                       int32_t n_recent, int32_t recent_num, int32_t recent_den, const void* k_full,
                                       const void* v_full, int32_t* idx_out, vlc_stream stream) {
     if (!cache) return fail(VLC_ERR_INVALID_ARG, "%s: cache is NULL", who);
     if (!scores || !k || !k_full || !v_full)
         return fail(VLC_ERR_INVALID_ARG, "%s: scores, k, k_full and v_full must not be NULL", who);
     hipStream_t hs = (hipStream_t)stream;
-    hipError_t e = vlc::launch_topk_compact(*cache, scores, k, n_recent, recent_num, recent_den, k_full, v_full, idx_out, hs);
+    hipError_t e = vlc::launch_topk_compact(*cache, lens, scores, k, n_recent, recent_num, recent_den, k_full, v_full, idx_out, hs);
     if (e != hipSuccess) return hip_fail(e, who);
     cache->compacted = true;
+    cache->ragged = lens != nullptr;
     memset(cache->appended, 0, sizeof(cache->appended));
     return VLC_OK;
 }
 
 vlc_status vlc_topk_compact(vlc_cache* cache, const float* scores, const int32_t* k, int32_t n_recent,
                             const void* k_full, const void* v_full, int32_t* idx_out, vlc_stream stream) {
+    const int32_t* lens = cache ? cache->shape.lens : nullptr;      // the array given at vlc_cache_create, read at every compaction
     if (n_recent < 0) return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact: n_recent = %d is negative", n_recent);
-    return topk_compact_common("vlc_topk_compact", cache, scores, k, n_recent, 0, 0, k_full, v_full, idx_out, stream);
+    return topk_compact_common("vlc_topk_compact", cache, lens, scores, k, n_recent, 0, 0, k_full, v_full, idx_out, stream);
 }
 
 vlc_status vlc_topk_compact_recent_frac(vlc_cache* cache, const float* scores, const int32_t* k, int32_t recent_num,
                                         int32_t recent_den, const void* k_full, const void* v_full,
                                         int32_t* idx_out, vlc_stream stream) {
+    const int32_t* lens = cache ? cache->shape.lens : nullptr;      // the array given at vlc_cache_create, read at every compaction
     if (recent_den < 1 || recent_num < 0 || recent_num > recent_den)
         return fail(VLC_ERR_INVALID_ARG, "vlc_topk_compact_recent_frac: fraction %d/%d is outside [0, 1]", recent_num, recent_den);
-    return topk_compact_common("vlc_topk_compact_recent_frac", cache, scores, k, 0, recent_num, recent_den, k_full, v_full,
+    return topk_compact_common("vlc_topk_compact_recent_frac", cache, lens, scores, k, 0, recent_num, recent_den, k_full, v_full,
                                idx_out, stream);
 }
 

@@ -94,6 +94,19 @@ __device__ __forceinline__ uint32_t wave_allreduce_sum_u32(uint32_t x) {
     return x;
 }
 
+// Prompt length and window length of request b: the shape's m and tau, or the request's own pair
+// from the optional per-request array, clamped into [1, m] and [1, min(tau, m_b)] so that no
+// kernel indexes outside the padded tensors whatever the array holds.
+struct ReqLen { int m, tau; };
+__device__ __forceinline__ ReqLen request_len(const int32_t* __restrict__ lens, int b, int m, int tau) {
+    ReqLen r{m, tau};
+    if (lens) {
+        r.m = min(max(lens[2 * b], 1), m);
+        r.tau = min(max(lens[2 * b + 1], 1), min(tau, r.m));
+    }
+    return r;
+}
+
 // Device-visible sticky error: first writer wins.
 __device__ __forceinline__ void set_sticky(int32_t* status, int code, int b, int l, int detail) {
     if (atomicCAS(status, 0, code) == 0) { status[1] = b; status[2] = l; status[3] = detail; }

@@ -43,6 +43,7 @@ struct CacheDev {                      // device pointers into the caller's aren
     int32_t* row_item_first;           // [B*L*Hkv]
     float* partials;                   // [max_items][g][d + 2]
     int32_t* counters;                 // [B*L*Hkv]
+    int32_t* lens;                     // [B][2] copy of the per-request (m_b, tau_b) of the last compaction
 };
 
 }  // namespace vlc
@@ -58,6 +59,7 @@ struct vlc_cache {
     vlc_cache_layout layout;
     vlc::CacheDev dev;
     bool compacted;
+    bool ragged;                       // the last compaction had per-request lengths (dev.lens is valid)
     int32_t appended[vlc::kMaxLayers]; // decode appends so far, per layer
 };
 
@@ -89,12 +91,13 @@ hipError_t launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t st);
 hipError_t launch_gamma(const vlc_shape& s, const uint64_t* nnz, float* gamma, hipStream_t st);
 
 // ---- allocation ----
-hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t B_tot,
+hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t alpha_num, int64_t alpha_den,
                            int32_t* k_out, float* beta_out, hipStream_t st);
 
 // ---- eviction ----
 // recent_den > 0: the recent window is floor(k * recent_num / recent_den) per (b, l), n_recent is ignored
-hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const int32_t* k,
+// lens: per-request (m_b, tau_b) of this compaction (device, may be null); copied into the cache
+hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const float* scores, const int32_t* k,
                                int32_t n_recent, int32_t recent_num, int32_t recent_den,
                                const void* k_full, const void* v_full, int32_t* idx_out, hipStream_t st);
 

@@ -34,6 +34,7 @@ struct MfmaArgs {
     const float* row_sum;
     float* scores;           // may be null
     unsigned long long* nnz; // may be null
+    const int32_t* lens;     // per-request (m_b, tau_b), or null
     float log2p;
     int L, Hq, Hkv, g, m, tau, tauP, RP, keys_per_split, nsplit;
     int rb0;                 // first 32-row block of this launch (a launch covers at most 16 of them)
@@ -45,13 +46,13 @@ struct MfmaArgs {
 __device__ __forceinline__ bf16x8_t as_frag(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
 
 template <int WAVES, int RB>
-__device__ __forceinline__ void load_q_frags(const MfmaArgs& a, int bl, int hkv, int wave, int lane, uint4 (&qf)[RB][kKSteps]) {
+__device__ __forceinline__ void load_q_frags(const MfmaArgs& a, int bl, int hkv, int wave, int lane, int tb, uint4 (&qf)[RB][kKSteps]) {
     const int half = lane >> 5;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int r = (a.rb0 + wave * RB + rb) * 32 + (lane & 31);
         const int hl = r / a.tauP, iw = r % a.tauP;
-        const bool ok = hl < a.g && iw < a.tau;
+        const bool ok = hl < a.g && iw < tb;
         const bf16_t* row = a.q_win + (((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0)) * kD;
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks)
@@ -109,30 +110,32 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 0) void rowstats_mfma_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;     // wave index in a scalar register
     const float c = (a.sm_scale ? a.sm_scale[l] : rsqrtf((float)kD)) * kLog2e;
     const bf16_t* kg = a.k + (size_t)group * a.m * kD;
+    const ReqLen rl = request_len(a.lens, bl / a.L, a.m, a.tau);
+    const int mb = rl.m, tb = rl.tau;                       // this request's prompt and window length
     const int k_begin = split * a.keys_per_split;
-    const int k_end = min(a.m, k_begin + a.keys_per_split);
+    const int k_end = min(mb, k_begin + a.keys_per_split);
 
     uint4 qf[RB][kKSteps];
-    load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, qf);
+    load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, tb, qf);
     // this lane's query row per row block, and the last key it may see (causal mask of Alg. 1)
     int jlim[RB];
     float m_run[RB], z_run[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const int r = (a.rb0 + wave * RB + rb) * 32 + (lane & 31);
-        jlim[rb] = a.m - a.tau + (r % a.tauP);
+        jlim[rb] = mb - tb + (r % a.tauP);
         m_run[rb] = -INFINITY;
         z_run[rb] = 0.f;
     }
 
     KStage<THREADS> st;
-    if (k_begin < k_end) st.load(kg, k_begin, a.m);
+    if (k_begin < k_end) st.load(kg, k_begin, mb);
     for (int kc = k_begin; kc < k_end; kc += kChunk) {
         __syncthreads();                                   // previous chunk fully consumed
         st.store(sK);
         __syncthreads();
-        if (kc + kChunk < k_end) st.load(kg, kc + kChunk, a.m);
-        const bool masked = kc + kChunk > a.m - a.tau + 1;     // chunk reaches past the first window key
+        if (kc + kChunk < k_end) st.load(kg, kc + kChunk, mb);
+        const bool masked = kc + kChunk > mb - tb + 1;     // chunk reaches past the first window key
 #pragma unroll 1
         for (int t = 0; t < kChunk / 32; ++t) {
             if (kc + t * 32 >= k_end) break;
@@ -187,13 +190,15 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 0) void rowstats_mfma_
 __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
                                            float* __restrict__ row_sum, float* __restrict__ row_max_t,
                                            int groups, int nsplit, int RP, int tauP, int tau, int g, int Hq, int Hkv,
-                                           uint64_t* __restrict__ nnz_clear, size_t n_clear) {
+                                           uint64_t* __restrict__ nnz_clear, size_t n_clear,
+                                           const int32_t* __restrict__ lens, int L, int m) {
     const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (x < n_clear) nnz_clear[x] = 0;
     if (x >= (size_t)groups * RP) return;
     const int r = (int)(x % RP), group = (int)(x / RP);
     const int hl = r / tauP, iw = r % tauP;
-    if (hl >= g || iw >= tau) return;
+    const int hkv = group % Hkv, bl = group / Hkv;
+    if (hl >= g || iw >= request_len(lens, bl / L, m, tau).tau) return;
     float M = -INFINITY;
     for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part[((size_t)group * nsplit + s) * RP + r].x);
     float Z = 0.f;
@@ -201,7 +206,6 @@ __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, floa
         const float2 p = part[((size_t)group * nsplit + s) * RP + r];
         if (p.x > -INFINITY) Z += p.y * exp2_fast(p.x - M);
     }
-    const int hkv = group % Hkv, bl = group / Hkv;
     const size_t o = ((size_t)bl * Hq + (size_t)hkv * g + hl) * tau + iw;
     row_max[o] = M * kLn2;
     row_sum[o] = Z;
@@ -220,11 +224,13 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;     // wave index in a scalar register
     const float c = (a.sm_scale ? a.sm_scale[l] : rsqrtf((float)kD)) * kLog2e;
     const bf16_t* kg = a.k + (size_t)group * a.m * kD;
+    const ReqLen rl = request_len(a.lens, bl / a.L, a.m, a.tau);
+    const int mb = rl.m, tb = rl.tau;                       // this request's prompt and window length
     const int k_begin = split * a.keys_per_split;
-    const int k_end = min(a.m, k_begin + a.keys_per_split);
+    const int k_end = min(mb, k_begin + a.keys_per_split);
 
     uint4 qf[RB][kKSteps];
-    load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, qf);
+    load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, tb, qf);
     // per accumulator slot: exponent offset (+inf for padded rows) and 1 / row sum
     float mc[RB][16], iz[RB][16];
     uint32_t cnt[RB];
@@ -235,7 +241,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
         for (int i = 0; i < 16; ++i) {
             const int r = (a.rb0 + wave * RB + rb) * 32 + acc_row(i, lane);
             const int hl = r / a.tauP, iw = r % a.tauP;
-            const bool ok = hl < a.g && iw < a.tau;
+            const bool ok = hl < a.g && iw < tb;
             const size_t o = ((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0);
             const float mt = a.row_max_t ? a.row_max_t[o] : a.row_max[o] * kLog2e;
             mc[rb][i] = ok ? mt : INFINITY;
@@ -244,13 +250,13 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     }
 
     KStage<THREADS> st;
-    if (k_begin < k_end) st.load(kg, k_begin, a.m);
+    if (k_begin < k_end) st.load(kg, k_begin, mb);
     for (int kc = k_begin; kc < k_end; kc += kChunk) {
         __syncthreads();
         st.store(sK);
         __syncthreads();
-        if (kc + kChunk < k_end) st.load(kg, kc + kChunk, a.m);
-        const bool masked = kc + kChunk > a.m - a.tau + 1;
+        if (kc + kChunk < k_end) st.load(kg, kc + kChunk, mb);
+        const bool masked = kc + kChunk > mb - tb + 1;
 #pragma unroll 1
         for (int t = 0; t < kChunk / 32; ++t) {
             uint4 kf[kKSteps];
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(qf[rb][ks]), as_frag(kf[ks]), acc, 0, 0, 0);
                 // acc[i] = <q_row, k_key>, row = row block base + acc_row(i), key = this lane's
                 if (masked) {
-                    const int base = a.m - a.tau + ((a.rb0 + wave * RB + rb) * 32) % a.tauP;
+                    const int base = mb - tb + ((a.rb0 + wave * RB + rb) * 32) % a.tauP;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const bool valid = key <= base + acc_row(i, lane);
@@ -295,6 +301,11 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
             float* dst = a.scores + (size_t)group * a.m + kc + threadIdx.x;
             *dst = a.accumulate ? *dst + s : s;
         }
+    }
+    // keys of the padded prompt beyond this request's own length score zero
+    if (a.scores && a.lens) {
+        const int z_end = min(a.m, k_begin + a.keys_per_split);
+        for (int j = max(k_begin, mb) + (int)threadIdx.x; j < z_end; j += THREADS) a.scores[(size_t)group * a.m + j] = 0.f;
     }
     if (a.nnz) {
 #pragma unroll
@@ -342,6 +353,7 @@ MfmaArgs make_args(const ScoreArgs& a, const Plan& p) {
     m.row_max = a.row_max; m.row_sum = a.row_sum; m.row_max_t = nullptr;
     m.scores = a.scores; m.nnz = (unsigned long long*)a.nnz;
     m.log2p = log2f(a.p);
+    m.lens = s.lens;
     m.L = s.L; m.Hq = s.Hq; m.Hkv = s.Hkv; m.g = s.Hq / s.Hkv; m.m = s.m; m.tau = s.tau;
     m.tauP = p.tauP; m.RP = p.RP; m.keys_per_split = p.keys_per_split; m.nsplit = p.nsplit;
     m.rb0 = 0; m.accumulate = 0;
@@ -383,7 +395,7 @@ hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
     const size_t n = (size_t)groups * p.RP;
     rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
         m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv,
-        a.nnz, a.nnz ? (size_t)s.B * s.L * s.Hq : 0);
+        a.nnz, a.nnz ? (size_t)s.B * s.L * s.Hq : 0, s.lens, s.L, s.m);
     return hipGetLastError();
 }
 

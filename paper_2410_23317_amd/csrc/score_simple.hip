@@ -52,7 +52,8 @@ __device__ __forceinline__ float dot_lds(const float* qrow, const float (&kr)[D]
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rowstats_simple_kernel(
     const T* __restrict__ q_win, const T* __restrict__ k, const float* __restrict__ sm_scale,
-    float2* __restrict__ part, int L, int Hq, int Hkv, int m, int tau, int nchunks) {
+    float2* __restrict__ part, int L, int Hq, int Hkv, int m, int tau, int nchunks,
+    const int32_t* __restrict__ lens) {
     __shared__ __align__(16) float qs[kRT * D];
     __shared__ float2 red[kRT][4];
     const int r = blockIdx.x / nchunks, chunk = blockIdx.x % nchunks;      // r = (b*L + l)*Hq + h; 1-D grid: rows * chunks
@@ -61,19 +62,21 @@ __global__ __launch_bounds__(256) void rowstats_simple_kernel(
     const int j = chunk * kScoreChunk + threadIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const float scale = sm_scale ? sm_scale[l] : rsqrtf((float)D);
-    const T* krow = k + (((size_t)bl * Hkv + h / g) * m + (j < m ? j : 0)) * D;
+    const ReqLen rl = request_len(lens, bl / L, m, tau);
+    const int mb = rl.m, tb = rl.tau;                       // this request's prompt and window length
+    const T* krow = k + (((size_t)bl * Hkv + h / g) * m + (j < mb ? j : 0)) * D;
     const T* qh = q_win + (size_t)r * tau * D;
     float kr[D];
-    load_key_row<T, D>(krow, j < m, kr);
-    for (int i0 = 0; i0 < tau; i0 += kRT) {
-        const int n = min(kRT, tau - i0);
+    load_key_row<T, D>(krow, j < mb, kr);
+    for (int i0 = 0; i0 < tb; i0 += kRT) {
+        const int n = min(kRT, tb - i0);
         __syncthreads();
         stage_q<T, D>(qh, i0, n, qs);
         __syncthreads();
         for (int ii = 0; ii < n; ++ii) {
             const int i = i0 + ii;
             const float s = dot_lds<D>(qs + ii * D, kr) * scale;
-            const bool valid = (j < m) && (j <= m - tau + i);
+            const bool valid = (j < mb) && (j <= mb - tb + i);
             const float wmax = wave_allreduce_max(valid ? s : -INFINITY);
             const float e = valid ? exp2_fast((s - wmax) * kLog2e) : 0.f;
             const float wsum = wave_allreduce_sum(e);
@@ -98,10 +101,12 @@ __global__ __launch_bounds__(256) void rowstats_simple_kernel(
 // n_clear threads also zero the per-head counters that the second sweep adds into.
 __global__ void rowstats_merge_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
                                       float* __restrict__ row_sum, size_t rows, int nchunks,
-                                      uint64_t* __restrict__ nnz_clear, size_t n_clear) {
+                                      uint64_t* __restrict__ nnz_clear, size_t n_clear,
+                                      const int32_t* __restrict__ lens, int LHq, int m, int tau) {
     const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (x < n_clear) nnz_clear[x] = 0;
     if (x >= rows) return;
+    if ((int)(x % tau) >= request_len(lens, (int)(x / tau / LHq), m, tau).tau) return;      // window row beyond this request's
     const float2* p = part + x * nchunks;
     float M = -INFINITY;
     for (int c = 0; c < nchunks; ++c) M = fmaxf(M, p[c].x);
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(256) void colsweep_simple_kernel(
     const T* __restrict__ q_win, const T* __restrict__ k, const float* __restrict__ sm_scale,
     const float* __restrict__ row_max, const float* __restrict__ row_sum,
     float* __restrict__ scores, unsigned long long* __restrict__ nnz, float lnp,
-    int L, int Hq, int Hkv, int m, int tau) {
+    int L, int Hq, int Hkv, int m, int tau, const int32_t* __restrict__ lens) {
     __shared__ __align__(16) float qs[kRT * D];
     __shared__ float ms[kRT], izs[kRT];
     const int nchunks = (m + kScoreChunk - 1) / kScoreChunk;
@@ -129,16 +134,18 @@ __global__ __launch_bounds__(256) void colsweep_simple_kernel(
     const int j = chunk * kScoreChunk + threadIdx.x;
     const int lane = threadIdx.x & 63;
     const float scale = sm_scale ? sm_scale[l] : rsqrtf((float)D);
-    const T* krow = k + ((size_t)rk * m + (j < m ? j : 0)) * D;
+    const ReqLen rl = request_len(lens, bl / L, m, tau);
+    const int mb = rl.m, tb = rl.tau;
+    const T* krow = k + ((size_t)rk * m + (j < mb ? j : 0)) * D;
     float kr[D];
-    load_key_row<T, D>(krow, j < m, kr);
+    load_key_row<T, D>(krow, j < mb, kr);
     float psi = 0.f;
     for (int hh = 0; hh < g; ++hh) {
         const size_t r = (size_t)bl * Hq + hkv * g + hh;
         const T* qh = q_win + r * tau * D;
         uint32_t cnt = 0;
-        for (int i0 = 0; i0 < tau; i0 += kRT) {
-            const int n = min(kRT, tau - i0);
+        for (int i0 = 0; i0 < tb; i0 += kRT) {
+            const int n = min(kRT, tb - i0);
             __syncthreads();
             stage_q<T, D>(qh, i0, n, qs);
             if (threadIdx.x < n) {
@@ -149,7 +156,7 @@ __global__ __launch_bounds__(256) void colsweep_simple_kernel(
             for (int ii = 0; ii < n; ++ii) {
                 const int i = i0 + ii;
                 const float s = dot_lds<D>(qs + ii * D, kr) * scale;
-                const bool valid = (j < m) && (j <= m - tau + i);
+                const bool valid = (j < mb) && (j <= mb - tb + i);
                 const float dlt = s - ms[ii];
                 if (valid) {
                     psi += exp2_fast(dlt * kLog2e) * izs[ii];
@@ -171,9 +178,12 @@ __global__ void fill_u64_kernel(uint64_t* p, size_t n, uint64_t v) {
 }
 
 __global__ void gamma_kernel(const uint64_t* __restrict__ nnz, float* __restrict__ gamma, size_t n,
-                             double inv_region) {
+                             const int32_t* __restrict__ lens, int LHq, int m, int tau) {
     const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (x < n) gamma[x] = (float)(1.0 - (double)nnz[x] * inv_region);
+    if (x >= n) return;
+    const ReqLen rl = request_len(lens, (int)(x / LHq), m, tau);
+    const double region = (double)rl.tau * (rl.m - rl.tau) + (double)rl.tau * (rl.tau + 1) / 2.0;   // entries of the causal region, Alg. 1
+    gamma[x] = (float)(1.0 - (double)nnz[x] / region);
 }
 
 template <typename T, int D>
@@ -183,10 +193,10 @@ hipError_t rowstats_impl(const ScoreArgs& a) {
     const size_t rows = (size_t)s.B * s.L * s.Hq * s.tau;
     const unsigned grid = (unsigned)nchunks * (unsigned)(s.B * s.L * s.Hq);
     rowstats_simple_kernel<T, D><<<grid, 256, 0, a.stream>>>(
-        (const T*)a.q_win, (const T*)a.k, a.sm_scale, (float2*)a.workspace, s.L, s.Hq, s.Hkv, s.m, s.tau, nchunks);
+        (const T*)a.q_win, (const T*)a.k, a.sm_scale, (float2*)a.workspace, s.L, s.Hq, s.Hkv, s.m, s.tau, nchunks, s.lens);
     rowstats_merge_kernel<<<(unsigned)((rows + 255) / 256), 256, 0, a.stream>>>(
         (const float2*)a.workspace, a.row_max, a.row_sum, rows, nchunks, a.nnz,
-        a.nnz ? (size_t)s.B * s.L * s.Hq : 0);
+        a.nnz ? (size_t)s.B * s.L * s.Hq : 0, s.lens, s.L * s.Hq, s.m, s.tau);
     return hipGetLastError();
 }
 
@@ -197,7 +207,7 @@ hipError_t colsweep_impl(const ScoreArgs& a) {
     const unsigned grid = (unsigned)nchunks * (unsigned)(s.B * s.L * s.Hkv);
     colsweep_simple_kernel<T, D><<<grid, 256, 0, a.stream>>>(
         (const T*)a.q_win, (const T*)a.k, a.sm_scale, a.row_max, a.row_sum, a.scores,
-        (unsigned long long*)a.nnz, logf(a.p), s.L, s.Hq, s.Hkv, s.m, s.tau);
+        (unsigned long long*)a.nnz, logf(a.p), s.L, s.Hq, s.Hkv, s.m, s.tau, s.lens);
     return hipGetLastError();
 }
 
@@ -229,8 +239,7 @@ hipError_t launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t st) {
 
 hipError_t launch_gamma(const vlc_shape& s, const uint64_t* nnz, float* gamma, hipStream_t st) {
     const size_t n = (size_t)s.B * s.L * s.Hq;
-    const double region = (double)s.tau * (s.m - s.tau) + (double)s.tau * (s.tau + 1) / 2.0;
-    gamma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(nnz, gamma, n, 1.0 / region);
+    gamma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(nnz, gamma, n, s.lens, s.L * s.Hq, s.m, s.tau);
     return hipGetLastError();
 }
 

@@ -16,7 +16,8 @@ namespace {
 // Everything is staged in LDS so that the serial prefix sums never wait on global memory.
 constexpr int kLayoutMaxBL = 2048;     // B*L entries staged in LDS; larger batches take the global path
 
-__global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, int B, int L, int Hkv, int m,
+__global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, const int32_t* __restrict__ lens,
+                                                     int B, int L, int Hkv, int m, int tau,
                                                      int d, int T_max, int64_t slots_per_request, int unit_slots,
                                                      int64_t max_items, CacheDev dev) {
     __shared__ int32_t sKept[kLayoutMaxBL];
@@ -31,9 +32,19 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
     if (tid < 4) dev.status[tid] = 0;
     if (tid == 0) sBad = 0;
     __syncthreads();
+    // per-request lengths: checked here (the only place with an error channel), kept in the cache
+    for (int b = tid; b < B; b += blockDim.x) {
+        int mb = m, tb = tau;
+        if (lens) {
+            mb = lens[2 * b]; tb = lens[2 * b + 1];
+            if (mb < 1 || mb > m || tb < 1 || tb > tau || tb > mb) set_sticky(dev.status, VLC_ERR_INVALID_ARG, b, -2, mb);
+        }
+        const ReqLen rl = request_len(lens, b, m, tau);
+        dev.lens[2 * b] = rl.m; dev.lens[2 * b + 1] = rl.tau;
+    }
     for (int x = tid; x < BL; x += blockDim.x) {
         int kk = k[x];
-        if (kk < 1 || kk > m) {
+        if (kk < 1 || kk > request_len(lens, x / L, m, tau).m) {
             set_sticky(dev.status, VLC_ERR_INVALID_ARG, x / L, x % L, kk);
             kk = 0;
         }
@@ -185,7 +196,7 @@ __device__ __forceinline__ void for_keys(const uint32_t (&key)[NK > 0 ? NK : 1],
 // lie in S*: hits_out[row] = |kept ∩ S*|.
 template <int NK, bool HIT>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, CacheDev dev,
-                                                             int Hkv, int m, int T_max, int n_recent,
+                                                             int L, int Hkv, int m, int ragged, int T_max, int n_recent,
                                                              int recent_num, int recent_den,
                                                              int32_t* __restrict__ idx_out,
                                                              int32_t* __restrict__ hits_out, float* __restrict__ rate_out) {
@@ -206,7 +217,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     // forced recent window: a count, or a fraction of this layer's budget (Sec. 5: 10 % of the budget)
     const int rcnt = HIT ? 0 : recent_den > 0 ? (int)((int64_t)kk * recent_num / recent_den) : min(max(n_recent, 0), kk);
     const int need = kk - rcnt;                // picked by score among positions [0, mc)
-    const int mc = m - rcnt;
+    const int mb = ragged ? dev.lens[2 * (bl / L)] : m;     // this request's prompt length (validated by the layout kernel)
+    const int mc = mb - rcnt;
     const int cap = kk + T_max;
     const float* s = scores + (size_t)row * m;
     int32_t* out = dev.idx + dev.slot_off[bl] * Hkv + (int64_t)hkv * cap;
@@ -405,16 +417,16 @@ __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_
 
 }  // namespace
 
-hipError_t launch_topk_compact(const vlc_cache& c, const float* scores, const int32_t* k, int32_t n_recent,
+hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const float* scores, const int32_t* k, int32_t n_recent,
                                int32_t recent_num, int32_t recent_den, const void* k_full, const void* v_full,
                                int32_t* idx_out, hipStream_t st) {
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
-    layout_kernel<<<1, 256, 0, st>>>(k, s.B, s.L, s.Hkv, s.m, s.d, c.T_max, c.slots_per_request, c.unit_slots,
+    layout_kernel<<<1, 256, 0, st>>>(k, lens, s.B, s.L, s.Hkv, s.m, s.tau, s.d, c.T_max, c.slots_per_request, c.unit_slots,
                                c.max_items, c.dev);
     // values per lane of a wave's segment (an eighth of the row, rounded up to whole wave loads)
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_SELECT(NK) select_kernel<NK, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.Hkv, s.m, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr)
+#define VLC_SELECT(NK) select_kernel<NK, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr)
     if (per_lane <= 8) VLC_SELECT(8);
     else if (per_lane <= 24) VLC_SELECT(24);
     else if (per_lane <= 64) VLC_SELECT(64);
@@ -436,7 +448,7 @@ hipError_t launch_cache_hit_count(const vlc_cache& c, const float* scores_star, 
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_HITS(NK) select_kernel<NK, true><<<rows, kSelThreads, 0, st>>>(scores_star, c.dev, s.Hkv, s.m, c.T_max, 0, 0, 0, nullptr, hits_out, rate_out)
+#define VLC_HITS(NK) select_kernel<NK, true><<<rows, kSelThreads, 0, st>>>(scores_star, c.dev, s.L, s.Hkv, s.m, c.ragged, c.T_max, 0, 0, 0, nullptr, hits_out, rate_out)
     if (per_lane <= 8) VLC_HITS(8);
     else if (per_lane <= 24) VLC_HITS(24);
     else if (per_lane <= 64) VLC_HITS(64);

@@ -22,8 +22,9 @@ class VLCachePath:
 
     def __init__(self, shape: V.vlc_shape, alpha: Tuple[int, int] = (1, 10), p: float = 0.01,
                  T_max: int = 128, n_recent: int = 0, device: str = "cuda", want_idx: bool = False,
-                 recent_frac: Optional[Tuple[int, int]] = None):
+                 recent_frac: Optional[Tuple[int, int]] = None, lens: Optional[torch.Tensor] = None):
         s = shape
+        self.lens = lens                      # the [B, 2] tensor behind shape.lens (ragged batches), kept alive here
         self.shape, self.alpha, self.p, self.T_max, self.n_recent = s, alpha, float(p), int(T_max), int(n_recent)
         self.recent_frac = recent_frac        # (num, den): recent window = floor(k_l * num / den) per layer
         dev = torch.device(device)
@@ -82,10 +83,14 @@ class VLCachePath:
         returns (hits [B,L,Hkv] int32, rate [B,L,Hkv] float32, scores_star [B,L,Hkv,m])."""
         s = self.shape
         if not hasattr(self, "_star"):
-            one = V.make_shape(s.B, s.L, s.Hq, s.Hkv, s.d, s.m, 1, "f32" if s.dtype == V.VLC_F32 else "bf16")
+            lens1 = None
+            if self.lens is not None:             # same prompt lengths, a one-row window for every request
+                lens1 = self.lens.clone()
+                lens1[:, 1] = 1
+            one = V.make_shape(s.B, s.L, s.Hq, s.Hkv, s.d, s.m, 1, "f32" if s.dtype == V.VLC_F32 else "bf16", lens=lens1)
             dev = self.scores.device
             self._star = dict(
-                shape=one, scores=torch.empty_like(self.scores),
+                shape=one, lens=lens1, scores=torch.empty_like(self.scores),
                 row_max=torch.empty((s.B, s.L, s.Hq, 1), dtype=torch.float32, device=dev),
                 row_sum=torch.empty((s.B, s.L, s.Hq, 1), dtype=torch.float32, device=dev),
                 workspace=torch.empty(V.vlc_workspace_bytes(one), dtype=torch.uint8, device=dev),
