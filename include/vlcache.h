@@ -12,7 +12,8 @@
  * Conventions shared by every call
  *   - Tensor arguments are DEVICE pointers owned by the caller, contiguous (row-major) in
  *     the stated layout, 16-byte aligned.  The library keeps no pointer after a call returns,
- *     except for the arena handed to vlc_cache_create.
+ *     except for the arena and the shape's optional lens array handed to vlc_cache_create
+ *     (lens is read again by every vlc_topk_compact on that cache).
  *   - Every call only enqueues work on the given HIP stream and returns; no call
  *     synchronises, allocates or frees device memory (vlc_cache_status synchronises, and says so).
  *   - Calls return a vlc_status; nothing throws or aborts.  vlc_last_error_string() holds a
