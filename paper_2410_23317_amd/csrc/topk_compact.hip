@@ -14,7 +14,7 @@ namespace {
 // One block for the whole batch (B*L is a few hundred entries): clears the sticky status, validates
 // the budgets, lays the slabs of each request out back to back, and builds the decode work list.
 // Everything is staged in LDS so that the serial prefix sums never wait on global memory.
-constexpr int kLayoutMaxBL = 2048;     // B*L entries staged in LDS; larger batches take the global path
+constexpr int kLayoutMaxBL = 2048;     // B*L entries staged in LDS (the shape check admits no larger batch)
 
 __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, const int32_t* __restrict__ lens,
                                                      int B, int L, int Hkv, int m, int tau,
