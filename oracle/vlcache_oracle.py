@@ -21,7 +21,8 @@ worked two-layer budget example; TopK equals a full sort; decode equals a librar
 scaled-dot-product attention; full-budget decode equals uncompressed attention;
 every routine equals the pure-loop brute force on tiny inputs; the decode-query attention equals
 a library softmax; CacheHitRate is 1 for the optimal policy, 0 for a disjoint set, k/m-bounded
-and equal to a brute-force set intersection.
+and equal to a brute-force set intersection; the E4M3 table equals torch's float8_e4m3fn, the
+row quantiser equals torch's conversion of the scaled row, is idempotent and within half a step.
 
 Parity unpinned by the paper (self-consistency only): the reduction of the g query
 heads of a GQA group into one KV-head score (sum; also used for the decode-query attention of
@@ -226,6 +227,52 @@ def cache_hit_rate(psi_star: np.ndarray, kept: np.ndarray, k: int) -> Tuple[int,
 
 
 # --------------------------------------------------------------------------------------
+# FP8 storage of the compressed cache  (App. A.2 names FP8 KV-cache quantisation as an
+# orthogonal technique that can be combined with sparsification; the format is this build's)
+# --------------------------------------------------------------------------------------
+
+def e4m3_values() -> np.ndarray:
+    """The 256 values of the OCP FP8 E4M3 format (1 sign, 4 exponent bits with bias 7, 3 mantissa
+    bits, no infinities, 0x7f / 0xff are NaN), from the format's definition."""
+    out = np.empty(256)
+    for c in range(256):
+        e, mnt = (c >> 3) & 0xF, c & 7
+        if e == 0xF and mnt == 7:
+            v = np.nan
+        elif e == 0:
+            v = mnt * 2.0 ** -9
+        else:
+            v = (1 + mnt / 8.0) * 2.0 ** (e - 7)
+        out[c] = -v if c & 0x80 else v
+    return out
+
+
+def quantize_e4m3_rows(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-row scaled E4M3: for every row (last axis) scale = absmax / 448 in fp32 (1 for an
+    all-zero row), code = the E4M3 value nearest to fp32(x / scale), ties to the even code,
+    magnitudes clamped to 448.  Returns (codes uint8, scales float32)."""
+    x = np.asarray(x, dtype=np.float32)
+    absmax = np.max(np.abs(x), axis=-1, keepdims=True).astype(np.float32)
+    scale = np.where(absmax > 0, absmax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    y = (x / scale).astype(np.float32)
+    a = np.minimum(np.abs(y), np.float32(448.0)).astype(np.float64)
+    pos = e4m3_values()[:0x7F]                       # the 127 finite non-negative values, ascending
+    hi = np.searchsorted(pos, a, side="left")        # pos[hi - 1] < a <= pos[hi]
+    hi = np.minimum(hi, len(pos) - 1)
+    lo = np.maximum(hi - 1, 0)
+    d_lo, d_hi = a - pos[lo], pos[hi] - a
+    code = np.where(d_lo < d_hi, lo, np.where(d_lo > d_hi, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(a == pos[hi], hi, code).astype(np.uint8)
+    code = np.where(np.signbit(y), code | 0x80, code).astype(np.uint8)
+    return code, scale[..., 0]
+
+
+def dequantize_e4m3_rows(code: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """x_hat = value(code) * scale, in fp64."""
+    return e4m3_values()[np.asarray(code, dtype=np.uint8)] * np.asarray(scale, dtype=np.float64)[..., None]
+
+
+# --------------------------------------------------------------------------------------
 # Decode attention over the compressed cache  (Sec. 2.1 decoding phase)
 # --------------------------------------------------------------------------------------
 
@@ -252,8 +299,9 @@ class CompressedCache:
     then attend over all slots; nothing is evicted during decode (allocation happens
     once, right after prefill)."""
 
-    def __init__(self, B: int, L: int, Hkv: int):
+    def __init__(self, B: int, L: int, Hkv: int, fp8: bool = False):
         self.B, self.L, self.Hkv = B, L, Hkv
+        self.fp8 = fp8            # rows are stored as per-row scaled E4M3 and attended as dequantised
         self.kc: List[List[List[Optional[np.ndarray]]]] = [[[None] * Hkv for _ in range(L)] for _ in range(B)]
         self.vc: List[List[List[Optional[np.ndarray]]]] = [[[None] * Hkv for _ in range(L)] for _ in range(B)]
         self.idx: List[List[List[Optional[np.ndarray]]]] = [[[None] * Hkv for _ in range(L)] for _ in range(B)]
@@ -264,6 +312,9 @@ class CompressedCache:
             idx = topk(psi_kv[h], int(k_l), n_recent)
             self.idx[b][l][h] = idx
             self.kc[b][l][h], self.vc[b][l][h] = compact(k[h], v[h], idx)
+            if self.fp8:
+                self.kc[b][l][h] = dequantize_e4m3_rows(*quantize_e4m3_rows(self.kc[b][l][h]))
+                self.vc[b][l][h] = dequantize_e4m3_rows(*quantize_e4m3_rows(self.vc[b][l][h]))
 
     def decode_layer(self, l: int, q: np.ndarray, k_new: Optional[np.ndarray], v_new: Optional[np.ndarray],
                      scale: float) -> np.ndarray:
@@ -272,8 +323,12 @@ class CompressedCache:
         for b in range(self.B):
             if k_new is not None:
                 for h in range(self.Hkv):
-                    self.kc[b][l][h] = np.concatenate([self.kc[b][l][h], np.asarray(k_new)[b, h][None]], axis=0)
-                    self.vc[b][l][h] = np.concatenate([self.vc[b][l][h], np.asarray(v_new)[b, h][None]], axis=0)
+                    kn, vn = np.asarray(k_new)[b, h][None], np.asarray(v_new)[b, h][None]
+                    if self.fp8:              # quantised on append, attended as stored
+                        kn = dequantize_e4m3_rows(*quantize_e4m3_rows(kn))
+                        vn = dequantize_e4m3_rows(*quantize_e4m3_rows(vn))
+                    self.kc[b][l][h] = np.concatenate([self.kc[b][l][h], kn], axis=0)
+                    self.vc[b][l][h] = np.concatenate([self.vc[b][l][h], vn], axis=0)
             out[b] = decode_attn(q[b], self.kc[b][l], self.vc[b][l], scale)
         return out
 

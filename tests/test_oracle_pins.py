@@ -282,6 +282,33 @@ def test_cache_hit_rate_definition():
     assert O.cache_hit_rate(tied, np.array([0, 3]), 2) == (1, 0.5)
 
 
+def test_e4m3_table_and_row_quantiser():
+    # the format table against a library's float8 type, the quantiser against that library's conversion
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    mine = O.e4m3_values()
+    assert np.array_equal(np.isnan(lib), np.isnan(mine)) and np.array_equal(lib[~np.isnan(lib)], mine[~np.isnan(mine)])
+    assert mine[0x38] == 1.0 and mine[0x7E] == 448.0 and mine[0x01] == 2.0 ** -9 and mine[0x08] == 2.0 ** -6
+    r = np.random.default_rng(12)
+    x = (r.standard_normal((200, 128)) * 10.0 ** r.uniform(-3, 3, size=(200, 1))).astype(np.float32)
+    x[3] = 0.0                                                                  # an all-zero row
+    code, scale = O.quantize_e4m3_rows(x)
+    assert scale.dtype == np.float32 and scale[3] == 1.0 and np.all(code[3] == 0)
+    np.testing.assert_array_equal(scale[np.arange(200) != 3], (np.abs(x).max(1) / np.float32(448.0))[np.arange(200) != 3])
+    y = np.clip((x / scale[:, None]).astype(np.float32), -448, 448)
+    want = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(code, want)
+    # the largest element of a row maps to +-448, the error is at most half a step of the local binade
+    xh = O.dequantize_e4m3_rows(code, scale)
+    assert np.all(np.abs(mine[code]).max(1)[np.arange(200) != 3] == 448.0)
+    step = np.maximum(2.0 ** np.floor(np.log2(np.maximum(np.abs(y), 2.0 ** -6))) / 8.0, 2.0 ** -9)
+    assert np.all(np.abs(xh - x) <= (0.5 * step + 1e-6) * scale[:, None] * 1.0001)
+    # halfway cases go to the even code; quantising a dequantised row changes nothing
+    c2, s2 = O.quantize_e4m3_rows(np.array([[448.0, 1.0625, 1.1875, 2.0 ** -10 * 1.0, 0.0]], dtype=np.float32))
+    assert s2[0] == 1.0 and c2[0].tolist() == [0x7E, 0x38, 0x3A, 0x00, 0x00]
+    c3, s3 = O.quantize_e4m3_rows(xh.astype(np.float32))
+    np.testing.assert_array_equal(O.dequantize_e4m3_rows(c3, s3), xh)
+
+
 def test_compact_is_a_gather():
     _, k, v = rand_case(2, m=19)
     idx = np.array([0, 3, 4, 18])
