@@ -146,13 +146,26 @@ typedef struct vlc_cache vlc_cache;
 size_t     vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max);
 vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
                             void* arena, size_t arena_bytes, vlc_cache** out);
+
+/* The same cache with its K/V rows stored as FP8 (paper App. A.2 names FP8 KV-cache quantisation as an
+ * orthogonal technique that combines with sparsification; this halves the bytes a decode step reads).
+ * Format: OCP E4M3 codes, one fp32 scale per row (slot and KV head): scale = absmax(row) / 448
+ * (1 for an all-zero row), code = nearest E4M3 value to fp32(x / scale), ties to even.  Rows are
+ * quantised when vlc_topk_compact gathers them and when a decode step appends; decode attends over
+ * the dequantised values code * scale.  bf16 storage only (VLC_ERR_DTYPE otherwise).  Every other
+ * call takes such a cache unchanged. */
+size_t     vlc_cache_bytes_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max);
+vlc_status vlc_cache_create_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
+                                void* arena, size_t arena_bytes, vlc_cache** out);
 void       vlc_cache_destroy(vlc_cache* cache);      /* frees host bookkeeping only */
 
 /* Where things live inside the arena (byte offsets from its base), for tests and tools.
  * Slab of (b,l): cap = k[b][l] + T_max slots; K rows of KV head h start at
  *   kv_off + ((slot_off[b][l] * 2 * Hkv) + h * cap) * d * elem_size,
  * V rows at the same plus Hkv * cap * d * elem_size; kept indices of head h at
- *   idx_off + (slot_off[b][l] * Hkv + h * cap) * 4.   Appended slots hold index m + t. */
+ *   idx_off + (slot_off[b][l] * Hkv + h * cap) * 4.   Appended slots hold index m + t.
+ * FP8 caches: elem_size is 1, and the fp32 scale of the K row in slot r of head h sits at
+ *   scale_off + (slot_off[b][l] * 2 * Hkv + h * cap + r) * 4, that of the V row Hkv * cap floats later. */
 typedef struct {
     size_t status_off;     /* int32[4]: sticky vlc_status, request, layer, detail */
     size_t slot_off_off;   /* int64[B*L]: first slot of (b,l), in slots            */
@@ -162,6 +175,8 @@ typedef struct {
     size_t scratch_off;
     size_t total_bytes;
     int64_t slots_per_request;
+    size_t scale_off;      /* FP8 caches only */
+    int32_t kv_fp8;        /* 1 if the rows are FP8 E4M3 codes */
 } vlc_cache_layout;
 vlc_status vlc_cache_get_layout(const vlc_cache* cache, vlc_cache_layout* out);
 

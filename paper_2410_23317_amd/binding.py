@@ -35,7 +35,8 @@ class vlc_shape(C.Structure):
 class vlc_cache_layout(C.Structure):
     _fields_ = [("status_off", C.c_size_t), ("slot_off_off", C.c_size_t), ("kept_off", C.c_size_t),
                 ("kv_off", C.c_size_t), ("idx_off", C.c_size_t), ("scratch_off", C.c_size_t),
-                ("total_bytes", C.c_size_t), ("slots_per_request", C.c_int64)]
+                ("total_bytes", C.c_size_t), ("slots_per_request", C.c_int64), ("scale_off", C.c_size_t),
+                ("kv_fp8", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -59,6 +60,10 @@ def _load() -> C.CDLL:
     lib.vlc_cache_bytes.argtypes = [shp, i32, i64]
     lib.vlc_cache_create.restype = C.c_int
     lib.vlc_cache_create.argtypes = [shp, i32, i64, vp, sz, C.POINTER(vp)]
+    lib.vlc_cache_bytes_fp8.restype = sz
+    lib.vlc_cache_bytes_fp8.argtypes = [shp, i32, i64]
+    lib.vlc_cache_create_fp8.restype = C.c_int
+    lib.vlc_cache_create_fp8.argtypes = [shp, i32, i64, vp, sz, C.POINTER(vp)]
     lib.vlc_cache_destroy.restype = None
     lib.vlc_cache_destroy.argtypes = [vp]
     lib.vlc_cache_get_layout.restype = C.c_int
@@ -145,16 +150,23 @@ def vlc_cache_bytes(shape, T_max, sum_k_max) -> int:
     return n
 
 
+def vlc_cache_bytes_fp8(shape, T_max, sum_k_max) -> int:
+    n = lib.vlc_cache_bytes_fp8(C.byref(shape), int(T_max), int(sum_k_max))
+    if n == 0:
+        raise VlcError(VLC_ERR_INVALID_ARG, vlc_last_error_string())
+    return n
+
+
 class Cache:
     """Owns the arena tensor and the library's host-side handle."""
 
-    def __init__(self, shape: vlc_shape, T_max: int, sum_k_max: int, device="cuda"):
-        self.shape, self.T_max, self.sum_k_max = shape, int(T_max), int(sum_k_max)
-        nbytes = vlc_cache_bytes(shape, T_max, sum_k_max)
+    def __init__(self, shape: vlc_shape, T_max: int, sum_k_max: int, device="cuda", fp8: bool = False):
+        self.shape, self.T_max, self.sum_k_max, self.fp8 = shape, int(T_max), int(sum_k_max), bool(fp8)
+        nbytes = (vlc_cache_bytes_fp8 if fp8 else vlc_cache_bytes)(shape, T_max, sum_k_max)
         self.arena = torch.empty(nbytes, dtype=torch.uint8, device=device)
         handle = C.c_void_p()
-        _check(lib.vlc_cache_create(C.byref(shape), self.T_max, self.sum_k_max, self.arena.data_ptr(), nbytes,
-                                    C.byref(handle)))
+        create = lib.vlc_cache_create_fp8 if fp8 else lib.vlc_cache_create
+        _check(create(C.byref(shape), self.T_max, self.sum_k_max, self.arena.data_ptr(), nbytes, C.byref(handle)))
         self.handle = handle
         lay = vlc_cache_layout()
         _check(lib.vlc_cache_get_layout(self.handle, C.byref(lay)))
@@ -174,6 +186,10 @@ class Cache:
 
 def vlc_cache_create(shape, T_max, sum_k_max, device="cuda") -> Cache:
     return Cache(shape, T_max, sum_k_max, device)
+
+
+def vlc_cache_create_fp8(shape, T_max, sum_k_max, device="cuda") -> Cache:
+    return Cache(shape, T_max, sum_k_max, device, fp8=True)
 
 
 def vlc_cache_status(cache: Cache) -> None:

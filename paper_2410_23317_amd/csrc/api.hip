@@ -175,13 +175,14 @@ struct ArenaPlan {
     int64_t max_items;
 };
 
-static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, ArenaPlan* plan) {
+static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, bool fp8, ArenaPlan* plan) {
     if (vlc_status st = check_shape(s)) return st;
+    if (fp8 && s->dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "an FP8 cache needs bf16 storage of Q, K and V");
     if (T_max < 0 || T_max > (1 << 24)) return fail(VLC_ERR_INVALID_ARG, "T_max = %d is out of range", T_max);
     if (sum_k_max < s->L || sum_k_max > (int64_t)s->L * s->m)
         return fail(VLC_ERR_INVALID_ARG, "sum_k_max = %lld is outside [L, L*m]", (long long)sum_k_max);
     vlc_cache_layout* lay = &plan->lay;
-    const size_t es = elem_size(s->dtype);
+    const size_t es = fp8 ? 1 : elem_size(s->dtype);          // bytes per cached K/V element
     const size_t BL = (size_t)s->B * s->L;
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
     // decode block-unit: 256 slots, 512 once the mean row is long (measured on the ragged budgets of
@@ -207,30 +208,33 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     plan->partials_off = off;     off = align_up(off + (size_t)plan->max_items * g * (s->d + 2) * sizeof(float), 256);
     plan->counters_off = off;     off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
     plan->lens_off = off;         off = align_up(off + (size_t)s->B * 2 * sizeof(int32_t), 256);
+    lay->scale_off = off;
+    if (fp8) off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * sizeof(float), 256);
+    lay->kv_fp8 = fp8 ? 1 : 0;
     lay->total_bytes = off;
     lay->slots_per_request = spr;
     return VLC_OK;
 }
 
-size_t vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
+static size_t cache_bytes_common(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, bool fp8) {
     ArenaPlan plan;
-    if (cache_layout(shape, T_max, sum_k_max, &plan) != VLC_OK) return 0;
+    if (cache_layout(shape, T_max, sum_k_max, fp8, &plan) != VLC_OK) return 0;
     return plan.lay.total_bytes;
 }
 
-vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
-                            size_t arena_bytes, vlc_cache** out) {
-    if (!out) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: out is NULL");
+static vlc_status cache_create_common(const char* who, const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, bool fp8,
+                                      void* arena, size_t arena_bytes, vlc_cache** out) {
+    if (!out) return fail(VLC_ERR_INVALID_ARG, "%s: out is NULL", who);
     *out = nullptr;
     ArenaPlan plan;
-    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, &plan)) return st;
+    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, fp8, &plan)) return st;
     const vlc_cache_layout& lay = plan.lay;
-    if (!arena) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: arena is NULL");
-    if (((uintptr_t)arena & 255) != 0) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: arena must be 256-byte aligned");
+    if (!arena) return fail(VLC_ERR_INVALID_ARG, "%s: arena is NULL", who);
+    if (((uintptr_t)arena & 255) != 0) return fail(VLC_ERR_INVALID_ARG, "%s: arena must be 256-byte aligned", who);
     if (arena_bytes < lay.total_bytes)
-        return fail(VLC_ERR_CAPACITY, "vlc_cache_create: arena of %zu bytes, %zu needed", arena_bytes, lay.total_bytes);
+        return fail(VLC_ERR_CAPACITY, "%s: arena of %zu bytes, %zu needed", who, arena_bytes, lay.total_bytes);
     vlc_cache* c = new (std::nothrow) vlc_cache;
-    if (!c) return fail(VLC_ERR_INVALID_ARG, "vlc_cache_create: out of host memory");
+    if (!c) return fail(VLC_ERR_INVALID_ARG, "%s: out of host memory", who);
     memset(c, 0, sizeof(*c));
     c->shape = *shape;
     c->T_max = T_max;
@@ -252,10 +256,27 @@ vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k
     c->dev.partials = (float*)(c->arena + plan.partials_off);
     c->dev.counters = (int32_t*)(c->arena + plan.counters_off);
     c->dev.lens = (int32_t*)(c->arena + plan.lens_off);
+    c->dev.scales = (float*)(c->arena + lay.scale_off);
+    c->kv_fp8 = fp8;
     c->ragged = false;
     c->compacted = false;
     *out = c;
     return VLC_OK;
+}
+
+size_t vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
+    return cache_bytes_common(shape, T_max, sum_k_max, false);
+}
+size_t vlc_cache_bytes_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
+    return cache_bytes_common(shape, T_max, sum_k_max, true);
+}
+vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
+                            size_t arena_bytes, vlc_cache** out) {
+    return cache_create_common("vlc_cache_create", shape, T_max, sum_k_max, false, arena, arena_bytes, out);
+}
+vlc_status vlc_cache_create_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
+                                size_t arena_bytes, vlc_cache** out) {
+    return cache_create_common("vlc_cache_create_fp8", shape, T_max, sum_k_max, true, arena, arena_bytes, out);
 }
 
 void vlc_cache_destroy(vlc_cache* cache) { delete cache; }

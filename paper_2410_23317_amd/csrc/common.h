@@ -81,6 +81,56 @@ __device__ __forceinline__ float group_allreduce_sum(float x) {
     return x;
 }
 
+// Max over groups of 8 or 16 consecutive lanes; every lane of the group gets the result.
+template <int LANES>
+__device__ __forceinline__ float group_allreduce_max(float x) {
+    static_assert(LANES == 8 || LANES == 16, "group size");
+    if constexpr (LANES == 16) {
+        x = fmaxf(x, dpp_mov<kDppRowRor(8)>(x));
+        x = fmaxf(x, dpp_mov<kDppRowRor(4)>(x));
+        x = fmaxf(x, dpp_mov<kDppRowRor(2)>(x));
+        x = fmaxf(x, dpp_mov<kDppRowRor(1)>(x));
+    } else {
+        x = fmaxf(x, dpp_mov<kDppRowHalfMirror>(x));
+        x = fmaxf(x, dpp_mov<kDppQuadPerm(1, 0, 3, 2)>(x));
+        x = fmaxf(x, dpp_mov<kDppQuadPerm(2, 3, 0, 1)>(x));
+    }
+    return x;
+}
+
+// ---- FP8 (OCP E4M3) rows with one fp32 scale per row -----------------------------------
+// Quantise the 8 bf16 values a lane holds of a row whose LPR lanes are consecutive:
+// scale = absmax(row) / 448 (1 for an all-zero row), code = E4M3 nearest to fp32(x / scale),
+// ties to even (v_cvt_pk_fp8_f32), magnitudes clamped to 448.  Byte e of the result is element e.
+template <int LPR>
+__device__ __forceinline__ uint2 quantize_row_e4m3(const uint4& v, float& scale) {
+    float f[8];
+    unpack16(v, f, (const bf16_t*)nullptr);
+    float amax = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
+    amax = group_allreduce_max<LPR>(amax);
+    scale = amax > 0.f ? amax / 448.0f : 1.0f;
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] = fminf(fmaxf(f[e] / scale, -448.0f), 448.0f);
+    int lo = 0, hi = 0;
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+    return make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
+// 8 E4M3 codes -> 8 bf16 values (exact: E4M3 has 3 mantissa bits), packed like a 16-byte bf16 chunk.
+__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(const uint2& r) {
+    const auto a = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.x, true);
+    const auto c = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, false), d = __builtin_amdgcn_cvt_pk_f32_fp8((int)r.y, true);
+    // upper halves of two fp32 words -> one word of two bf16 (first element in the low half)
+    auto pack = [](float lo, float hi) { return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u); };
+    return make_uint4(pack(a[0], a[1]), pack(b[0], b[1]), pack(c[0], c[1]), pack(d[0], d[1]));
+}
+
 __device__ __forceinline__ float wave_allreduce_max(float x) {
     for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
     return x;

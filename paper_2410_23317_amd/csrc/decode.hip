@@ -44,6 +44,7 @@ struct DecodeParams {
     int appended;            // appends before this call
     int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
     int prefetch;            // next tile's loads issued early (more registers, 2 blocks per CU)
+    int kv_fp8;              // the cache rows are E4M3 codes with per-row scales
     float default_scale;
 };
 
@@ -146,9 +147,14 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 template <typename T> struct IsBf16 { static constexpr bool value = false; };
 template <> struct IsBf16<bf16_t> { static constexpr bool value = true; };
 
-template <typename T, int D, int G, int NT, bool PF>
+// Q8: the cache rows are E4M3 codes with one fp32 scale per row (8 bytes per lane instead of 16); codes are
+// expanded to bf16 (exactly) where they are consumed, the K scale multiplies the finished logit, the
+// V scale the probability before it is rounded to bf16.  Appends to such a cache are done by
+// append_fp8_kernel before this kernel runs.
+template <typename T, int D, int G, int NT, bool PF, bool Q8>
 __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void decode_kernel(DecodeParams P) {
     constexpr bool BF = IsBf16<T>::value;
+    static_assert(!Q8 || BF, "FP8 caches hold bf16 models");
     constexpr int EP = Elem<T>::kPer16B;        // elements in a 16-byte chunk
     constexpr int LPR = D / EP;                 // lanes per K/V row
     constexpr int KPI = 64 / LPR;               // rows per wave load
@@ -201,6 +207,10 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
         const int new_slot = appending ? len - 1 : -1;
         const T* Kbase = reinterpret_cast<const T*>(P.dev.kv) + kbase;
         const T* Vbase = Kbase + (int64_t)P.Hkv * cap * D;
+        const uint8_t* K8 = reinterpret_cast<const uint8_t*>(P.dev.kv) + kbase;      // FP8 cache: one byte per element
+        const uint8_t* V8 = K8 + (int64_t)P.Hkv * cap * D;
+        const float* Ksc = P.dev.scales + kbase / D;
+        const float* Vsc = Ksc + (int64_t)P.Hkv * cap;
         const T* knew = reinterpret_cast<const T*>(P.k_new) + ((size_t)(lr * P.B + ib) * P.Hkv + hkv) * D;
         const T* vnew = reinterpret_cast<const T*>(P.v_new) + ((size_t)(lr * P.B + ib) * P.Hkv + hkv) * D;
         const float scale2 = (P.sm_scale ? P.sm_scale[il] : P.default_scale) * kLog2e;
@@ -223,7 +233,13 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
         // K and V of a tile sit in separate register buffers.  The K loads of the next tile are issued
         // as soon as the logits have consumed the current ones, the V loads as soon as P.V is done, so
         // a wave keeps 8 to 16 KB in flight while it computes.
-        uint4 kb[NIT], vb[NIT];
+        uint4 kb[Q8 ? 1 : NIT], vb[Q8 ? 1 : NIT];
+        uint2 kb8[Q8 ? NIT : 1], vb8[Q8 ? NIT : 1];
+        float ksc[Q8 ? NIT : 1], vsc[Q8 ? KK : 1];
+        auto load_row8 = [&](const uint8_t* base, int t0, int i) -> uint2 {
+            const int key = t0 + i * KPI + sub;
+            return (key < len) ? *reinterpret_cast<const uint2*>(base + (int64_t)key * D + c * 8) : make_uint2(0, 0);
+        };
         auto load_row = [&](auto fullc, const T* base, const T* fresh, int t0, int i) -> uint4 {
             constexpr bool FULL = decltype(fullc)::value;
             if constexpr (FULL) {
@@ -235,16 +251,35 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
             }
         };
         auto issue_k = [&](int t0) {
-            const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);   // wave-uniform
+            if constexpr (Q8) {
 #pragma unroll
-            for (int i = 0; i < NIT; ++i)
-                kb[i] = full ? load_row(std::true_type{}, Kbase, knew, t0, i) : load_row(std::false_type{}, Kbase, knew, t0, i);
+                for (int i = 0; i < NIT; ++i) {
+                    kb8[i] = load_row8(K8, t0, i);
+                    const int key = t0 + i * KPI + sub;
+                    ksc[i] = key < len ? Ksc[key] : 0.f;
+                }
+            } else {
+                const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);   // wave-uniform
+#pragma unroll
+                for (int i = 0; i < NIT; ++i)
+                    kb[i] = full ? load_row(std::true_type{}, Kbase, knew, t0, i) : load_row(std::false_type{}, Kbase, knew, t0, i);
+            }
         };
         auto issue_v = [&](int t0) {
-            const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);
+            if constexpr (Q8) {
 #pragma unroll
-            for (int i = 0; i < NIT; ++i)
-                vb[i] = full ? load_row(std::true_type{}, Vbase, vnew, t0, i) : load_row(std::false_type{}, Vbase, vnew, t0, i);
+                for (int i = 0; i < NIT; ++i) vb8[i] = load_row8(V8, t0, i);
+#pragma unroll
+                for (int kk = 0; kk < KK; ++kk) {
+                    const int key = t0 + scol + 16 * kk;          // the slots this lane owns in the softmax step
+                    vsc[kk] = key < len ? Vsc[key] : 0.f;
+                }
+            } else {
+                const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);
+#pragma unroll
+                for (int i = 0; i < NIT; ++i)
+                    vb[i] = full ? load_row(std::true_type{}, Vbase, vnew, t0, i) : load_row(std::false_type{}, Vbase, vnew, t0, i);
+            }
         };
         auto tile_body = [&](auto fullc, int t0, bool more) {
             constexpr bool FULL = decltype(fullc)::value;
@@ -254,12 +289,15 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                 const int key = t0 + i * KPI + sub;
                 const bool live = FULL || key < len;
                 float part[G];
+                uint4 kq;
+                float rs = scale2;                                  // logit scale, times the row's K scale for FP8 rows
+                if constexpr (Q8) { kq = e4m3x8_to_bf16x8(kb8[i]); rs *= ksc[i]; } else { kq = kb[i]; }
 #pragma unroll
-                for (int h = 0; h < G; ++h) part[h] = dot16<T>(kb[i], qv[h], 0.f);
+                for (int h = 0; h < G; ++h) part[h] = dot16<T>(kq, qv[h], 0.f);
                 if constexpr (SCATTER) {
                     const float tot = row16_reduce_scatter<G>(part, c);
                     const int hh = ((c >> 3) << 1) | ((c >> 2) & 1);
-                    if ((c & 3) == 0 && hh < G) sL[wave][i * KPI + sub][hh] = live ? tot * scale2 : -INFINITY;
+                    if ((c & 3) == 0 && hh < G) sL[wave][i * KPI + sub][hh] = live ? tot * rs : -INFINITY;
                 } else {
                     float mine = 0.f;
 #pragma unroll
@@ -267,7 +305,7 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                         const float tot = group_allreduce_sum<LPR>(part[h]);
                         mine = (c == h) ? tot : mine;
                     }
-                    if (c < G) sL[wave][i * KPI + sub][c] = live ? mine * scale2 : -INFINITY;
+                    if (c < G) sL[wave][i * KPI + sub][c] = live ? mine * rs : -INFINITY;
                 }
             }
             if (more) issue_k(t0 + 4 * TK);
@@ -297,7 +335,7 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                         const int slot = scol + 16 * kk, li = slot / KPI, ls = slot % KPI;
                         if constexpr (BF) {
                             // bf16 probability into its half of the pair word of loads (li & ~1, li | 1)
-                            const __bf16 pb = (__bf16)pr;
+                            const __bf16 pb = Q8 ? (__bf16)(pr * vsc[kk]) : (__bf16)pr;      // FP8 rows: the V scale rides on the probability
                             reinterpret_cast<uint16_t*>(&sPk[wave][(li >> 1) * KPI + ls][h % GP])[li & 1] =
                                 __builtin_bit_cast(uint16_t, pb);
                         } else {
@@ -325,8 +363,11 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                     uint32_t pk[G];
 #pragma unroll
                     for (int h = 0; h < G; ++h) pk[h] = pp[h];
-                    const uint32_t a[4] = {vb[i].x, vb[i].y, vb[i].z, vb[i].w};
-                    const uint32_t b[4] = {vb[i + 1].x, vb[i + 1].y, vb[i + 1].z, vb[i + 1].w};
+                    uint4 va, vbb;
+                    if constexpr (Q8) { va = e4m3x8_to_bf16x8(vb8[i]); vbb = e4m3x8_to_bf16x8(vb8[i + 1]); }
+                    else { va = vb[i]; vbb = vb[i + 1]; }
+                    const uint32_t a[4] = {va.x, va.y, va.z, va.w};
+                    const uint32_t b[4] = {vbb.x, vbb.y, vbb.z, vbb.w};
 #pragma unroll
                     for (int d2 = 0; d2 < 4; ++d2) {
                         const uint32_t lo = __builtin_amdgcn_perm(b[d2], a[d2], 0x05040100u);   // (a.even, b.even)
@@ -369,7 +410,7 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
         }
 
         // The unit that holds the new slot also stores the new row into the cache.
-        if (appending && new_slot >= key0 && new_slot < key0 + BK && wave == 0 && sub == 0) {
+        if (!Q8 && appending && new_slot >= key0 && new_slot < key0 + BK && wave == 0 && sub == 0) {
             T* kdst = const_cast<T*>(Kbase) + (int64_t)new_slot * D;
             T* vdst = const_cast<T*>(Vbase) + (int64_t)new_slot * D;
             *reinterpret_cast<uint4*>(kdst + c * EP) = *reinterpret_cast<const uint4*>(knew + c * EP);
@@ -440,6 +481,35 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
     }
 }
 
+// Append to an FP8 cache: one wave per (layer, request, KV head) row quantises the new key and value
+// (lanes [0, LPR) the key, [LPR, 2 LPR) the value) into slot kept + appended and records its position.
+template <int D>
+__global__ __launch_bounds__(64) void append_fp8_kernel(DecodeParams P) {
+    constexpr int LPR = D / 8;
+    const int row = blockIdx.x;
+    const int hkv = row % P.Hkv;
+    const int b = (row / P.Hkv) % P.B;
+    const int lr = row / (P.Hkv * P.B);
+    const int bl = b * P.L + P.layer_begin + lr;
+    const int kept = P.dev.kept[bl];
+    if (kept == 0) return;
+    const int cap = kept + P.T_max;
+    const int64_t so = P.dev.slot_off[bl];
+    const int64_t kbase = ((so * 2 * P.Hkv) + (int64_t)hkv * cap) * D;
+    const int slot = kept + P.appended;
+    const int lane = threadIdx.x, c = lane % LPR, which = lane / LPR;         // which: 0 key, 1 value, others idle
+    const bf16_t* src = reinterpret_cast<const bf16_t*>(which == 1 ? P.v_new : P.k_new) +
+                        ((size_t)(lr * P.B + b) * P.Hkv + hkv) * D + c * 8;
+    float scale;
+    const uint2 q = quantize_row_e4m3<LPR>(*reinterpret_cast<const uint4*>(src), scale);
+    if (which < 2) {
+        const int64_t voff = which ? (int64_t)P.Hkv * cap : 0;                  // value rows follow the key rows of the slab
+        *reinterpret_cast<uint2*>(P.dev.kv + kbase + voff * D + (int64_t)slot * D + c * 8) = q;
+        if (c == 0) P.dev.scales[kbase / D + voff + slot] = scale;
+    }
+    if (lane == 0) P.dev.idx[so * P.Hkv + (int64_t)hkv * cap + slot] = P.m + P.appended;
+}
+
 // Second kernel of merge mode 2: one block per (layer, request, KV head) row.
 template <typename T, int D, int G, int NT>
 __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
@@ -462,8 +532,15 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
 template <typename T, int D, int G, int NT>
 hipError_t launch_nt(const DecodeParams& P, int grid, int rows, hipStream_t st) {
 
-    if (P.prefetch && NT > 1) decode_kernel<T, D, G, NT, true><<<grid, 256, 0, st>>>(P);
-    else decode_kernel<T, D, G, NT, false><<<grid, 256, 0, st>>>(P);
+    if constexpr (IsBf16<T>::value) {
+        if (P.kv_fp8) {
+            decode_kernel<T, D, G, NT, false, true><<<grid, 256, 0, st>>>(P);
+            if (P.merge_mode == 2) decode_merge_kernel<T, D, G, NT><<<rows, 256, 0, st>>>(P);
+            return hipGetLastError();
+        }
+    }
+    if (P.prefetch && NT > 1) decode_kernel<T, D, G, NT, true, false><<<grid, 256, 0, st>>>(P);
+    else decode_kernel<T, D, G, NT, false, false><<<grid, 256, 0, st>>>(P);
     if (P.merge_mode == 2) decode_merge_kernel<T, D, G, NT><<<rows, 256, 0, st>>>(P);
     return hipGetLastError();
 }
@@ -515,6 +592,7 @@ hipError_t launch_decode(const DecodeArgs& a) {
     P.default_scale = 1.0f / sqrtf((float)s.d);
     P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knobs
     P.prefetch = env_int("VLC_DECODE_PREFETCH", 0);
+    P.kv_fp8 = c.kv_fp8 ? 1 : 0;
     const int rows = a.n_layers * s.B * s.Hkv;
     // Upper bound on the block-units of the layer range: every row at the full prompt length, and
     // never more than the whole work list.
@@ -524,6 +602,13 @@ hipError_t launch_decode(const DecodeArgs& a) {
     if (grid < 1) grid = 1;
     const int g = s.Hq / s.Hkv;
     const int nt = (int)(bk / 128);
+    if (c.kv_fp8 && a.k_new) {
+        // the new rows are quantised into their slots first; the attention kernel then sees them as cached
+        if (s.d == 64) append_fp8_kernel<64><<<rows, 64, 0, a.stream>>>(P);
+        else append_fp8_kernel<128><<<rows, 64, 0, a.stream>>>(P);
+        P.k_new = nullptr; P.v_new = nullptr;
+        P.appended = a.appended + 1;
+    }
     if (s.dtype == VLC_F32)
         return s.d == 64 ? launch_g<float, 64>(P, g, nt, (int)grid, rows, a.stream) : launch_g<float, 128>(P, g, nt, (int)grid, rows, a.stream);
     return s.d == 64 ? launch_g<bf16_t, 64>(P, g, nt, (int)grid, rows, a.stream) : launch_g<bf16_t, 128>(P, g, nt, (int)grid, rows, a.stream);

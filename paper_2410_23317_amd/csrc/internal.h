@@ -44,6 +44,7 @@ struct CacheDev {                      // device pointers into the caller's aren
     float* partials;                   // [max_items][g][d + 2]
     int32_t* counters;                 // [B*L*Hkv]
     int32_t* lens;                     // [B][2] copy of the per-request (m_b, tau_b) of the last compaction
+    float* scales;                     // FP8 caches: one fp32 scale per K row and per V row, laid out like the rows
 };
 
 }  // namespace vlc
@@ -59,6 +60,7 @@ struct vlc_cache {
     vlc_cache_layout layout;
     vlc::CacheDev dev;
     bool compacted;
+    bool kv_fp8;                       // rows stored as E4M3 codes + per-row scale
     bool ragged;                       // the last compaction had per-request lengths (dev.lens is valid)
     int32_t appended[vlc::kMaxLayers]; // decode appends so far, per layer
 };

@@ -415,6 +415,46 @@ __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_
     }
 }
 
+// The gather for an FP8 cache (bf16 source rows of D elements): same decomposition, each row is
+// quantised on the way (one fp32 scale per row, stored by the row's first lane).
+template <int D>
+__global__ __launch_bounds__(256) void gather_fp8_kernel(const char* __restrict__ k_full, const char* __restrict__ v_full,
+                                                         CacheDev dev, int L, int Hkv, int m, int T_max, int unit_slots) {
+    constexpr int LPR = D / 8;                  // lanes per row: 8 bf16 values (16 bytes) each
+    constexpr int RPB = 256 / LPR;
+    const int w = blockIdx.x;
+    const WorkItem it = dev.items[w];
+    if (w >= dev.layer_item_start[L]) return;
+    const int kk = it.kept, key0 = it.key0;
+    if (kk == 0 || key0 >= kk) return;
+    const int r_end = min(kk, key0 + unit_slots);
+    const int cap = kk + T_max;
+    uint2* kd = reinterpret_cast<uint2*>(dev.kv + it.kbase);                     // one byte per element
+    uint2* vd = kd + (int64_t)Hkv * cap * LPR;
+    float* ksc = dev.scales + it.kbase / D;
+    float* vsc = ksc + (int64_t)Hkv * cap;
+    const uint4* ks = reinterpret_cast<const uint4*>(k_full + (size_t)it.row_abs * m * D * 2);
+    const uint4* vs = reinterpret_cast<const uint4*>(v_full + (size_t)it.row_abs * m * D * 2);
+    const int32_t* idx = dev.idx + it.idx_base;
+    const int c = threadIdx.x % LPR, sub = threadIdx.x / LPR;
+    // every lane of a row group runs the same number of passes (the reductions are group-wide)
+    for (int r0 = key0; r0 < r_end; r0 += RPB) {
+        const int r = r0 + sub;
+        const bool live = r < r_end;
+        const int64_t j = live ? idx[r] : idx[r_end - 1];
+        const uint4 a = ks[j * LPR + c];
+        const uint4 b = vs[j * LPR + c];
+        float sa, sb;
+        const uint2 qa = quantize_row_e4m3<LPR>(a, sa);
+        const uint2 qb = quantize_row_e4m3<LPR>(b, sb);
+        if (live) {
+            kd[(int64_t)r * LPR + c] = qa;
+            vd[(int64_t)r * LPR + c] = qb;
+            if (c == 0) { ksc[r] = sa; vsc[r] = sb; }
+        }
+    }
+}
+
 }  // namespace
 
 hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const float* scores, const int32_t* k, int32_t n_recent,
@@ -437,6 +477,11 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
     const unsigned grid = (unsigned)c.max_items;
     const char* kf = (const char*)k_full;
     const char* vf = (const char*)v_full;
+    if (c.kv_fp8) {
+        if (s.d == 64) gather_fp8_kernel<64><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots);
+        else gather_fp8_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots);
+        return hipGetLastError();
+    }
     if (rowbytes == 128) gather_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
     else if (rowbytes == 256) gather_kernel<256><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
     else gather_kernel<512><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);

@@ -22,7 +22,8 @@ class VLCachePath:
 
     def __init__(self, shape: V.vlc_shape, alpha: Tuple[int, int] = (1, 10), p: float = 0.01,
                  T_max: int = 128, n_recent: int = 0, device: str = "cuda", want_idx: bool = False,
-                 recent_frac: Optional[Tuple[int, int]] = None, lens: Optional[torch.Tensor] = None):
+                 recent_frac: Optional[Tuple[int, int]] = None, lens: Optional[torch.Tensor] = None,
+                 kv_fp8: bool = False):
         s = shape
         self.lens = lens                      # the [B, 2] tensor behind shape.lens (ragged batches), kept alive here
         self.shape, self.alpha, self.p, self.T_max, self.n_recent = s, alpha, float(p), int(T_max), int(n_recent)
@@ -40,7 +41,7 @@ class VLCachePath:
         self.idx_out = torch.full((s.B, s.L, s.Hkv, s.m), -1, dtype=i32, device=dev) if want_idx else None
         b_tot = (alpha[0] * s.L * s.m) // alpha[1]
         self.sum_k_max = min(s.L * s.m, b_tot + s.L * k_min_tokens(s.m))
-        self.cache = V.vlc_cache_create(s, self.T_max, self.sum_k_max, device)
+        self.cache = (V.vlc_cache_create_fp8 if kv_fp8 else V.vlc_cache_create)(s, self.T_max, self.sum_k_max, device)
 
     # -- after prefill ---------------------------------------------------------------------
     def score(self, q_win, k, sm_scale) -> None:
@@ -104,19 +105,29 @@ class VLCachePath:
 
 def cache_layer_view(cache: V.Cache, b: int, l: int, appended: int = 0):
     """(Kc, Vc, idx) of request b, layer l as tensors [Hkv, n, d] / [Hkv, n] aliasing the arena,
-    n = kept + appended.  Pure address arithmetic over the layout the library reports."""
+    n = kept + appended.  Pure address arithmetic over the layout the library reports.  For an FP8
+    cache Kc and Vc are pairs (codes uint8 [Hkv, n, d], scales float32 [Hkv, n])."""
     s, lay, arena = cache.shape, cache.layout, cache.arena
     BL = s.B * s.L
     slot_off = arena[lay.slot_off_off: lay.slot_off_off + 8 * BL].view(torch.int64)
     kept = arena[lay.kept_off: lay.kept_off + 4 * BL].view(torch.int32)
     so, kk = int(slot_off[b * s.L + l]), int(kept[b * s.L + l])
     cap, n = kk + cache.T_max, kk + appended
+    ib = lay.idx_off + so * s.Hkv * 4
+    idx = arena[ib: ib + s.Hkv * cap * 4].view(torch.int32).view(s.Hkv, cap)[:, :n]
+    if lay.kv_fp8:
+        slab = s.Hkv * cap * s.d
+        kb = lay.kv_off + so * 2 * s.Hkv * s.d
+        kcodes = arena[kb: kb + slab].view(s.Hkv, cap, s.d)[:, :n]
+        vcodes = arena[kb + slab: kb + 2 * slab].view(s.Hkv, cap, s.d)[:, :n]
+        sb = lay.scale_off + so * 2 * s.Hkv * 4
+        ksc = arena[sb: sb + s.Hkv * cap * 4].view(torch.float32).view(s.Hkv, cap)[:, :n]
+        vsc = arena[sb + s.Hkv * cap * 4: sb + 2 * s.Hkv * cap * 4].view(torch.float32).view(s.Hkv, cap)[:, :n]
+        return (kcodes, ksc), (vcodes, vsc), idx
     dt = torch.float32 if s.dtype == V.VLC_F32 else torch.bfloat16
     es = 4 if s.dtype == V.VLC_F32 else 2
     slab = s.Hkv * cap * s.d * es
     kb = lay.kv_off + so * 2 * s.Hkv * s.d * es
     kc = arena[kb: kb + slab].view(dt).view(s.Hkv, cap, s.d)[:, :n]
     vc = arena[kb + slab: kb + 2 * slab].view(dt).view(s.Hkv, cap, s.d)[:, :n]
-    ib = lay.idx_off + so * s.Hkv * 4
-    idx = arena[ib: ib + s.Hkv * cap * 4].view(torch.int32).view(s.Hkv, cap)[:, :n]
     return kc, vc, idx
