@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--kv-fp8", action="store_true",
+                    help="store the compressed cache as FP8 E4M3 with per-row scales (a variant, never the default: "
+                         "the headline figures are those of the native bf16 cache)")
     ap.add_argument("--paper-grid", action="store_true",
                     help="run the (batch, prompt length) grid of the paper's speed benchmark (App. A.4) instead")
     args = ap.parse_args()
@@ -99,7 +102,7 @@ def main() -> int:
         del src, dst
 
     shape = V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
-    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=T)
+    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=T, kv_fp8=args.kv_fp8)
 
     def one_step(ev=None):
         if ev: ev[0].record()
@@ -165,10 +168,12 @@ def main() -> int:
     kk = path.k.cpu().numpy().astype(np.int64)                            # [B, L]
     mean_len = kk.sum() + cfg.B * cfg.L * (T + 1) / 2.0                   # sum over (b,l) of the mean slot count
     kv_bytes = 2.0 * cfg.Hkv * cfg.d * es * mean_len
+    if args.kv_fp8:                                                       # one byte per element plus one fp32 scale per row
+        kv_bytes = 2.0 * cfg.Hkv * (cfg.d + 4) * mean_len
     io_bytes = cfg.B * cfg.L * (2 * cfg.Hq + 2 * cfg.Hkv) * cfg.d * es
     alg_bytes = kv_bytes + io_bytes
     achieved = alg_bytes / (dec_launch_us * 1e-6) / 1e9
-    default_run = alpha == (1, 10) and T == 100 and cfg.cid in MEASURED_DECODE_TRAFFIC_MIB
+    default_run = alpha == (1, 10) and T == 100 and cfg.cid in MEASURED_DECODE_TRAFFIC_MIB and not args.kv_fp8
     traffic = int(MEASURED_DECODE_TRAFFIC_MIB[cfg.cid] * 1048576) if default_run else None
     roofline = {"bound": "hbm", "kernel": "decode_kernel (one ragged launch over all layers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -179,7 +184,7 @@ def main() -> int:
         "metric": METRIC, "value": round(comp_ms / cfg.B, 4), "unit": "ms/request (KV compress)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "vs_baseline": None, "dtype": cfg.dtype + (" (fp8 e4m3 kv cache)" if args.kv_fp8 else ""), "data": "synthetic",
         "config": {"workload": f"cfg{cfg.cid} {cfg.name}: B={cfg.B} L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} d={cfg.d} "
                                f"m={cfg.m} {cfg.layout()} tau={cfg.tau} alpha={alpha[0]}/{alpha[1]} p=0.01 "
                                f"decode_steps={T}"},
