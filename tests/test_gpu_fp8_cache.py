@@ -81,3 +81,50 @@ def test_fp8_cache_needs_bf16_storage():
     with pytest.raises(V.VlcError) as e:
         V.vlc_cache_create_fp8(shape, 2, 20)
     assert e.value.status in (V.VLC_ERR_DTYPE, V.VLC_ERR_INVALID_ARG)
+
+
+def test_fp8_cache_with_a_ragged_batch_and_a_recent_window():
+    """The options compose: per-request lengths, a recent window that is a tenth of each layer's budget,
+    FP8 storage.  Kept positions against the oracle's TopK on the GPU's own scores, stored rows
+    against the oracle's quantiser."""
+    import paper_2410_23317_amd as V
+    from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
+    lens = [(700, 30), (260, 12)]
+    cfgs = [W.custom_config(cid=410 + i, name=f"combo{i}", dtype="bf16", d=128, Hq=8, Hkv=2, L=2, B=1, m=m, tau=t,
+                            lead_text=6, n_visual=m - t - 12, sinks=3, alphas=((1, 5),)) for i, (m, t) in enumerate(lens)]
+    B, L, Hq, Hkv, d, m_max, tau_max = 2, 2, 8, 2, 128, 700, 30
+    dt = torch.bfloat16
+    q_win = torch.full((B, L, Hq, tau_max, d), float("nan"), dtype=dt, device="cuda")
+    k = torch.full((B, L, Hkv, m_max, d), float("nan"), dtype=dt, device="cuda")
+    v = torch.full_like(k, float("nan"))
+    host = {}
+    for b, cfg in enumerate(cfgs):
+        for l in range(L):
+            t = host[(b, l)] = W.layer_inputs(cfg, 0, l)
+            q_win[b, l, :, : cfg.tau].copy_(torch.from_numpy(t["q_win"]).to(dt))
+            k[b, l, :, : cfg.m].copy_(torch.from_numpy(t["k"]).to(dt))
+            v[b, l, :, : cfg.m].copy_(torch.from_numpy(t["v"]).to(dt))
+    sm = torch.from_numpy(W.sm_scale(cfgs[0])).cuda()
+    lens_t = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    shape = V.make_shape(B, L, Hq, Hkv, d, m_max, tau_max, "bf16", lens=lens_t)
+    path = VLCachePath(shape, alpha=(1, 5), T_max=2, want_idx=True, recent_frac=(1, 10), lens=lens_t, kv_fp8=True)
+    path.compress(q_win, k, v, sm)
+    path.status()
+    torch.cuda.synchronize()
+    scores, kk = path.scores.cpu().numpy(), path.k.cpu().numpy()
+    for b, cfg in enumerate(cfgs):
+        for l in range(L):
+            (kcod, ksc), (vcod, vsc), idx = cache_layer_view(path.cache, b, l)
+            idx = idx.cpu().numpy()
+            k_l = int(kk[b, l])
+            for h in range(Hkv):
+                want = O.topk(scores[b, l, h, : cfg.m].astype(np.float64), k_l, O.recent_count(k_l, 1, 10))
+                assert np.array_equal(idx[h], want), (b, l, h)
+                wk, wks = O.quantize_e4m3_rows(host[(b, l)]["k"][h][idx[h]])
+                assert np.array_equal(kcod[h].cpu().numpy(), wk) and np.array_equal(ksc[h].cpu().numpy(), wks)
+    out = torch.empty((L, B, Hq, d), dtype=dt, device="cuda")
+    q = torch.randn((L, B, Hq, d), device="cuda").to(dt)
+    kn = torch.randn((L, B, Hkv, d), device="cuda").to(dt)
+    path.decode(0, L, q, kn, kn, sm, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
