@@ -193,6 +193,8 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
         if (v == 128 || v == 256 || v == 512) plan->unit_slots = v;
     }
     plan->max_items = (int64_t)s->Hkv * ((int64_t)s->B * spr / plan->unit_slots + (int64_t)BL);
+    if (plan->max_items > (int64_t)1 << 30)
+        return fail(VLC_ERR_SHAPE, "cache of %lld decode units: budgets plus reserved appends are too large", (long long)plan->max_items);
     const int g = s->Hq / s->Hkv;
     size_t off = 0;
     lay->status_off = off;      off = align_up(off + 4 * sizeof(int32_t), 256);
