@@ -121,6 +121,35 @@ __device__ __forceinline__ float row16_reduce_scatter(const float (&v)[G], int c
     return r;                                           // total of head 2*bit3 + bit2
 }
 
+// The same for up to eight heads: three halving levels (lane bits 3, 2, 1 choose the heads a lane keeps,
+// the partner at c^8, c^7, c^2 supplies its share of them) and one plain add with c^1.  The partners'
+// offsets {8} x {7} x {2} x {1} reach all sixteen lanes.  Lane c ends with the total of head
+// 4 bit3 + 2 bit2 + bit1: 22 operations instead of 40 for eight separate all-reduces.
+template <int G>
+__device__ __forceinline__ float row16_reduce_scatter8(const float (&v)[G], int c) {
+    static_assert(G > 4 && G <= 8, "scatter form for five to eight heads");
+    const bool b3 = (c & 8) != 0, b2 = (c & 4) != 0, b1 = (c & 2) != 0;
+    float x[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x[j] = j < G ? v[j] : 0.f;
+    float a[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {                           // bit 3 clear keeps heads 0..3, set keeps 4..7
+        const float keep = b3 ? x[4 + j] : x[j], send = b3 ? x[j] : x[4 + j];
+        a[j] = keep + dpp_mov<kDppRowRor(8)>(send);
+    }
+    float b[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {                           // bit 2 picks the pair; partner c^7 has the other value of bit 2
+        const float keep = b2 ? a[2 + j] : a[j], send = b2 ? a[j] : a[2 + j];
+        b[j] = keep + dpp_mov<kDppRowHalfMirror>(send);
+    }
+    const float keep = b1 ? b[1] : b[0], send = b1 ? b[0] : b[1];
+    float r = keep + dpp_mov<kDppQuadPerm(2, 3, 0, 1)>(send);   // partner c^2: other value of bit 1
+    r += dpp_mov<kDppQuadPerm(1, 0, 3, 2)>(r);                  // partner c^1
+    return r;
+}
+
 // Max / sum over the 64 lanes of a wave from a DPP row all-reduce plus four lane reads.
 __device__ __forceinline__ float lane_value(float x, int l) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
@@ -298,6 +327,10 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                     const float tot = row16_reduce_scatter<G>(part, c);
                     const int hh = ((c >> 3) << 1) | ((c >> 2) & 1);
                     if ((c & 3) == 0 && hh < G) sL[wave][i * KPI + sub][hh] = live ? tot * rs : -INFINITY;
+                } else if constexpr (LPR == 16 && G > 4) {
+                    const float tot = row16_reduce_scatter8<G>(part, c);
+                    const int hh = ((c >> 3) << 2) | (((c >> 2) & 1) << 1) | ((c >> 1) & 1);
+                    if ((c & 1) == 0 && hh < G) sL[wave][i * KPI + sub][hh] = live ? tot * rs : -INFINITY;
                 } else {
                     float mine = 0.f;
 #pragma unroll
