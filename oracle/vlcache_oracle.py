@@ -22,7 +22,10 @@ scaled-dot-product attention; full-budget decode equals uncompressed attention;
 every routine equals the pure-loop brute force on tiny inputs; the decode-query attention equals
 a library softmax; CacheHitRate is 1 for the optimal policy, 0 for a disjoint set, k/m-bounded
 and equal to a brute-force set intersection; the E4M3 table equals torch's float8_e4m3fn, the
-row quantiser equals torch's conversion of the scaled row, is idempotent and within half a step.
+row quantiser equals torch's conversion of the scaled row, is idempotent and within half a step;
+the window attention equals a library scaled-dot-product attention under the same mask, returns
+V's row for a one-key prompt and 1 for constant V; the column sweep from given statistics equals
+the scores, and scales as 1/Z and exp(-M) in the statistics it is given.
 
 Parity unpinned by the paper (self-consistency only): the reduction of the g query
 heads of a GQA group into one KV-head score (sum; also used for the decode-query attention of
@@ -91,6 +94,34 @@ def score(q_win, k, scale):
     Hkv = np.asarray(k).shape[0]
     psi_kv = psi_h.reshape(Hkv, Hq // Hkv, -1).sum(axis=1)
     return psi_kv, psi_h, M, Z
+
+
+def window_attention(q_win, k, v, scale) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Causal prefill attention of the post-vision window rows: O[h, i] = sum_j A'_{ij} v[h // g, j]
+    (Sec. 2.1, prefill phase, restricted to the last tau prompt positions), together with the two
+    row statistics M and Z of the same softmax.  This is what a prefill attention kernel that also
+    emits its running max and sum for those rows would hand to the scoring sweep (App. A.3: the
+    first kernel computes exactly the reductions a fused-softmax attention kernel carries)."""
+    A, _, M, Z = post_vision_attention(q_win, k, scale)
+    vv = np.asarray(v, dtype=np.float64)
+    Hq, Hkv = A.shape[0], vv.shape[0]
+    g = Hq // Hkv
+    out = np.empty((Hq, A.shape[1], vv.shape[2]), dtype=np.float64)
+    for h in range(Hq):
+        out[h] = A[h] @ vv[h // g]
+    return out, M, Z
+
+
+def score_from_stats(q_win, k, scale, M: np.ndarray, Z: np.ndarray):
+    """The column sweep alone (App. A.3, second kernel): psi from logits and GIVEN row statistics,
+    psi_h[j] = sum_i exp(s_ij - M_i) / Z_i over the causal region.  Returns (psi_kv, psi_h)."""
+    s = logits(q_win, k, scale)
+    tau, m = s.shape[1], s.shape[2]
+    valid = causal_valid(m, tau)[None]
+    e = np.where(valid, np.exp(np.where(valid, s, -np.inf) - np.asarray(M, dtype=np.float64)[:, :, None]), 0.0)
+    psi_h = (e / np.asarray(Z, dtype=np.float64)[:, :, None]).sum(axis=1)
+    Hq, Hkv = psi_h.shape[0], np.asarray(k).shape[0]
+    return psi_h.reshape(Hkv, Hq // Hkv, -1).sum(axis=1), psi_h
 
 
 # --------------------------------------------------------------------------------------

@@ -394,3 +394,54 @@ def test_compress_request_wires_the_stages_in_order():
     assert nnz.shape == (3, 4) and len(psis) == 3
     assert list(kk) == list(O.allocate(nnz, 200, 1, 10)[0])
     assert nnz[0].sum() > nnz[2].sum() and kk[0] >= kk[2]      # sharper layers are sparser, get less
+
+
+# ---------------------------------------------------------------- window attention with row statistics
+
+def test_window_attention_equals_library_sdpa_with_the_causal_mask():
+    q, k, v = rand_case(71, Hq=6, Hkv=2, tau=7, m=29, d=16)
+    out, M, Z = O.window_attention(q, k, v, 0.21)
+    mask = torch.from_numpy(O.causal_valid(29, 7))
+    tq, tk, tv = (torch.from_numpy(x)[None] for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=0.21, enable_gqa=True)[0].numpy()
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    # the statistics are those of the scoring path: M + ln Z is the row's log-sum-exp
+    s = torch.from_numpy(O.logits(q, k, 0.21)).masked_fill(~mask, -math.inf)
+    np.testing.assert_allclose(M + np.log(Z), torch.logsumexp(s, dim=2).numpy(), rtol=1e-13)
+    np.testing.assert_allclose(M, s.max(dim=2).values.numpy(), rtol=0, atol=0)
+
+
+def test_window_attention_special_cases():
+    q, k, v = rand_case(72, Hq=4, Hkv=2, tau=4, m=12, d=8)
+    # constant values: every output row is that constant whatever the attention
+    out, _, _ = O.window_attention(q, k, np.full_like(v, 2.5), 0.4)
+    np.testing.assert_allclose(out, 2.5, rtol=1e-14)
+    # window = whole prompt: row 0 sees only key 0 and returns v[0]; row i averages v[:i+1] for equal logits
+    out, M, Z = O.window_attention(np.zeros((4, 12, 8)), k, v, 1.0)
+    for h in range(4):
+        for i in range(12):
+            np.testing.assert_allclose(out[h, i], v[h // 2, : i + 1].mean(axis=0), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(Z, np.arange(1, 13)[None].repeat(4, 0), rtol=1e-14)
+    assert np.all(M == 0.0)
+    # a key that dominates row i drags the output to its value row; keys after the row's position are invisible
+    kd = np.zeros((2, 12, 8)); kd[:, 3, 0] = 50.0; kd[:, 11, 0] = 80.0
+    qd = np.zeros((4, 4, 8)); qd[:, :, 0] = 1.0
+    out, _, _ = O.window_attention(qd, kd, v, 1.0)
+    np.testing.assert_allclose(out[:, :3], np.broadcast_to(v[[0, 0, 1, 1]][:, None, 3], (4, 3, 8)), rtol=0, atol=1e-12)     # rows 8..10 do not see key 11
+    np.testing.assert_allclose(out[:, 3], v[[0, 0, 1, 1], 11], rtol=0, atol=1e-10)              # row 11 does
+
+
+def test_score_from_stats_equals_scores_and_follows_its_statistics():
+    q, k, _ = rand_case(73, Hq=6, Hkv=3, tau=6, m=31, d=8)
+    psi_kv, psi_h, M, Z = O.score(q, k, 0.3)
+    kv2, h2 = O.score_from_stats(q, k, 0.3, M, Z)
+    np.testing.assert_allclose(h2, psi_h, rtol=1e-13, atol=1e-300)
+    np.testing.assert_allclose(kv2, psi_kv, rtol=1e-13, atol=1e-300)
+    # the sweep takes the statistics as given: doubling Z halves the scores, raising M by ln 2 halves them too
+    _, hz = O.score_from_stats(q, k, 0.3, M, 2.0 * Z)
+    np.testing.assert_allclose(hz, 0.5 * psi_h, rtol=1e-13)
+    _, hm = O.score_from_stats(q, k, 0.3, M + math.log(2.0), Z)
+    np.testing.assert_allclose(hm, 0.5 * psi_h, rtol=1e-12)
+    # and a library softmax under the mask, summed over the window rows
+    s = torch.from_numpy(O.logits(q, k, 0.3)).masked_fill(~torch.from_numpy(O.causal_valid(31, 6)), -math.inf)
+    np.testing.assert_allclose(h2, torch.softmax(s, dim=2).sum(dim=1).numpy(), rtol=1e-12)
