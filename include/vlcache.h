@@ -117,6 +117,40 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
                         void* workspace, size_t workspace_bytes, vlc_stream stream);
 
 /*
+ * vlc_window_attn -- causal prefill attention of the post-vision window rows that also hands out
+ * its row statistics (paper Sec. 2.1, prefill phase, for the last tau prompt positions; App. A.3:
+ * the first scoring kernel computes the two reductions a fused-softmax attention kernel carries
+ * anyway).  With it the row-statistics sweep of vlc_score is not needed: a model runs this call as
+ * the attention of its last tau prompt rows and then vlc_score_from_stats.
+ *
+ *   out[b,l,h,i,:] = sum over valid j of A'_ij * v[b,l,h/g,j,:]     (A', validity as under vlc_score)
+ *   row_max, row_sum = M_i, Z_i of the same softmax
+ *
+ * q_win   [B,L,Hq,tau,d]  in   bf16
+ * k, v    [B,L,Hkv,m,d]   in   bf16
+ * out     [B,L,Hq,tau,d]  out  bf16 (fp32 accumulation, probabilities rounded to bf16 for the product)
+ * row_max, row_sum [B,L,Hq,tau] out fp32
+ * workspace               scratch of at least vlc_window_attn_workspace_bytes(shape) bytes
+ * Built for dtype VLC_BF16 and d = 128 (VLC_ERR_UNIMPLEMENTED otherwise; the workspace query then
+ * returns 0).  With shape->lens, rows >= tau_b of request b are left untouched.
+ */
+size_t vlc_window_attn_workspace_bytes(const vlc_shape* shape);
+vlc_status vlc_window_attn(const vlc_shape* shape, const void* q_win, const void* k, const void* v,
+                           const float* sm_scale, void* out, float* row_max, float* row_sum,
+                           void* workspace, size_t workspace_bytes, vlc_stream stream);
+
+/*
+ * vlc_score_from_stats -- the column sweep of vlc_score alone (paper App. A.3, second kernel), for
+ * row statistics the caller already has (from vlc_window_attn, or from its own prefill attention):
+ * scores and nnz exactly as defined under vlc_score, with row_max (natural-log domain) and row_sum
+ * as INPUTS.  Any dtype and d the scoring path supports; needs no workspace.  nnz may be NULL.
+ */
+vlc_status vlc_score_from_stats(const vlc_shape* shape, const void* q_win, const void* k,
+                                const float* sm_scale, float p,
+                                const float* row_max, const float* row_sum,
+                                float* scores, uint64_t* nnz, vlc_stream stream);
+
+/*
  * vlc_allocate -- sparsity-aware layer budgets (paper Alg. 1, SkewedCacheBudgetAllocation),
  * in integers.  Per request: n_l = sum_h nnz[b,l,h] (proportional to 1 - gamma'_l),
  * N = sum_l n_l, B_tot = floor(alpha_num * L * m / alpha_den); floor quotas

@@ -54,6 +54,12 @@ def _load() -> C.CDLL:
     lib.vlc_score.argtypes = [shp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
     lib.vlc_sparsity.restype = C.c_int
     lib.vlc_sparsity.argtypes = [shp, vp, vp, vp, vp, f32, vp, vp, vp, sz, vp]
+    lib.vlc_window_attn_workspace_bytes.restype = sz
+    lib.vlc_window_attn_workspace_bytes.argtypes = [shp]
+    lib.vlc_window_attn.restype = C.c_int
+    lib.vlc_window_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.vlc_score_from_stats.restype = C.c_int
+    lib.vlc_score_from_stats.argtypes = [shp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
     lib.vlc_allocate.restype = C.c_int
     lib.vlc_allocate.argtypes = [shp, vp, i64, i64, vp, vp, vp]
     lib.vlc_cache_bytes.restype = sz
@@ -136,6 +142,24 @@ def vlc_sparsity(shape, q_win, k, sm_scale, row_max, p, nnz, gamma, workspace) -
     _check(lib.vlc_sparsity(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(sm_scale), _ptr(row_max), float(p),
                             _ptr(nnz), _ptr(gamma), _ptr(workspace),
                             0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def vlc_window_attn_workspace_bytes(shape: vlc_shape) -> int:
+    n = lib.vlc_window_attn_workspace_bytes(C.byref(shape))
+    if n == 0:
+        raise VlcError(VLC_ERR_UNIMPLEMENTED, vlc_last_error_string())
+    return n
+
+
+def vlc_window_attn(shape, q_win, k, v, sm_scale, out, row_max, row_sum, workspace) -> None:
+    _check(lib.vlc_window_attn(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(v), _ptr(sm_scale), _ptr(out),
+                               _ptr(row_max), _ptr(row_sum), _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def vlc_score_from_stats(shape, q_win, k, sm_scale, p, row_max, row_sum, scores, nnz) -> None:
+    _check(lib.vlc_score_from_stats(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(sm_scale), float(p), _ptr(row_max),
+                                    _ptr(row_sum), _ptr(scores), _ptr(nnz), _stream()))
 
 
 def vlc_allocate(shape, nnz, alpha_num, alpha_den, k_out, beta_out) -> None:

@@ -151,6 +151,53 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
     return VLC_OK;
 }
 
+size_t vlc_window_attn_workspace_bytes(const vlc_shape* shape) {
+    if (check_shape(shape) != VLC_OK) return 0;
+    if (!vlc::window_attn_supported(*shape)) {
+        fail(VLC_ERR_UNIMPLEMENTED, "vlc_window_attn: built for bf16 storage and d = 128 only");
+        return 0;
+    }
+    return vlc::window_attn_workspace_bytes(*shape);
+}
+
+vlc_status vlc_window_attn(const vlc_shape* shape, const void* q_win, const void* k, const void* v,
+                           const float* sm_scale, void* out, float* row_max, float* row_sum,
+                           void* workspace, size_t workspace_bytes, vlc_stream stream) {
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!vlc::window_attn_supported(*shape))
+        return fail(VLC_ERR_UNIMPLEMENTED, "vlc_window_attn: built for bf16 storage and d = 128 only");
+    if (!q_win || !k || !v || !out || !row_max || !row_sum || !workspace)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_window_attn: q_win, k, v, out, row_max, row_sum and workspace must not be NULL");
+    const size_t need = vlc::window_attn_workspace_bytes(*shape);
+    if (workspace_bytes < need)
+        return fail(VLC_ERR_CAPACITY, "vlc_window_attn: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    vlc::WindowAttnArgs a;
+    a.s = *shape; a.q_win = q_win; a.k = k; a.v = v; a.sm_scale = sm_scale; a.out = out;
+    a.row_max = row_max; a.row_sum = row_sum; a.workspace = workspace; a.stream = (hipStream_t)stream;
+    const hipError_t e = vlc::launch_window_attn(a);
+    if (e != hipSuccess) return hip_fail(e, "vlc_window_attn");
+    return VLC_OK;
+}
+
+vlc_status vlc_score_from_stats(const vlc_shape* shape, const void* q_win, const void* k, const float* sm_scale,
+                                float p, const float* row_max, const float* row_sum, float* scores, uint64_t* nnz,
+                                vlc_stream stream) {
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!q_win || !k || !row_max || !row_sum || !scores)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_score_from_stats: q_win, k, row_max, row_sum and scores must not be NULL");
+    if (nnz && !(p > 0.f && p < 1.f)) return fail(VLC_ERR_INVALID_ARG, "vlc_score_from_stats: p = %g is outside (0, 1)", p);
+    vlc::ScoreArgs a;
+    a.s = *shape; a.q_win = q_win; a.k = k; a.sm_scale = sm_scale; a.p = nnz ? p : 0.5f; a.scores = scores;
+    a.row_max = const_cast<float*>(row_max); a.row_sum = const_cast<float*>(row_sum); a.row_max_t = nullptr;
+    a.nnz = nnz; a.workspace = nullptr; a.stream = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (nnz) e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, a.stream);
+    if (e != hipSuccess) return hip_fail(e, "vlc_score_from_stats clear counts");
+    e = run_colsweep(a, ws_plan(*shape).mfma, false);
+    if (e != hipSuccess) return hip_fail(e, "vlc_score_from_stats column sweep");
+    return VLC_OK;
+}
+
 vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alpha_num, int64_t alpha_den,
                         int32_t* k_out, float* beta_out, vlc_stream stream) {
     if (vlc_status st = check_shape(shape)) return st;

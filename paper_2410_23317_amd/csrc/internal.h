@@ -92,6 +92,23 @@ hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t);
 hipError_t launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t st);
 hipError_t launch_gamma(const vlc_shape& s, const uint64_t* nnz, float* gamma, hipStream_t st);
 
+// ---- window attention with row statistics (matrix-core path only: bf16, d = 128) ----
+struct WindowAttnArgs {
+    vlc_shape s;
+    const void* q_win;
+    const void* k;
+    const void* v;
+    const float* sm_scale;      // may be null
+    void* out;                  // [B,L,Hq,tau,d]
+    float* row_max;
+    float* row_sum;
+    void* workspace;
+    hipStream_t stream;
+};
+bool window_attn_supported(const vlc_shape& s);
+size_t window_attn_workspace_bytes(const vlc_shape& s);
+hipError_t launch_window_attn(const WindowAttnArgs& a);
+
 // ---- allocation ----
 hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t alpha_num, int64_t alpha_den,
                            int32_t* k_out, float* beta_out, hipStream_t st);

@@ -67,6 +67,24 @@ def test_argument_validation_happens_before_any_launch(V):
     assert V.lib.vlc_allocate(sp, None, 1, 10, 1, None, None) == V.VLC_ERR_INVALID_ARG
 
 
+def test_window_attn_and_score_from_stats_validate_before_any_launch(V):
+    f32 = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
+    assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32)) == 0 and "bf16" in V.vlc_last_error_string()
+    assert V.lib.vlc_window_attn(C.byref(f32), 1, 1, 1, None, 1, 1, 1, 1, 1 << 30, None) == V.VLC_ERR_UNIMPLEMENTED
+    s = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16")
+    sp = C.byref(s)
+    need = V.vlc_window_attn_workspace_bytes(s)
+    assert need >= 2 * 2 * 4 * 32 * 128 * 4                      # at least one split of fp32 partial outputs
+    assert V.lib.vlc_window_attn(sp, 1, 1, None, None, 1, 1, 1, 1, need, None) == V.VLC_ERR_INVALID_ARG     # v missing
+    assert V.lib.vlc_window_attn(sp, 1, 1, 1, None, 1, 1, 1, 1, need - 1, None) == V.VLC_ERR_CAPACITY
+    big = V.make_shape(2, 32, 8, 8, 128, 3000, 32, "bf16")         # every KV group has a block of its own: no partials
+    assert V.vlc_window_attn_workspace_bytes(big) == 256
+    assert V.lib.vlc_score_from_stats(sp, 1, 1, None, 0.01, None, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
+    assert V.lib.vlc_score_from_stats(sp, 1, 1, None, 2.0, 1, 1, 1, 1, None) == V.VLC_ERR_INVALID_ARG
+    bad = V.make_shape(1, 2, 8, 3, 128, 3000, 32, "bf16")
+    assert V.lib.vlc_score_from_stats(C.byref(bad), 1, 1, None, 0.01, 1, 1, 1, None, None) == V.VLC_ERR_SHAPE
+
+
 def test_cache_bookkeeping_errors(V):
     s = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
     n = V.vlc_cache_bytes(s, 8, 120)
