@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_FLOPS = 2.5e15
 # HBM-side bytes of one all-layer decode launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # counter reads for a plain 256 MiB copy), measured offline on the default run of a config: 10 % budget,
 # 100 decode steps.  The figures and the commands are in profiles/all_kernels_cfg*.md.
-MEASURED_DECODE_TRAFFIC_MIB = {1: 45.09 + 1.27, 2: 551.79 + 7.33}
+MEASURED_DECODE_TRAFFIC_MIB = {1: 45.07 + 1.27, 2: 551.80 + 7.33}
 
 
 def main() -> int:
@@ -157,6 +157,24 @@ def main() -> int:
     score_flop = 2 * 2.0 * cfg.tau * cfg.d * cfg.m * cfg.Hq * cfg.B * cfg.L
     mfma_util = score_flop / (score_ms * 1e-3) / MFMA_BF16_PEAK_FLOPS if cfg.dtype == "bf16" else None
 
+    # ---- the fused route to the scores (bf16, d = 128): the attention of the window rows hands out the row
+    # statistics (it stands in for those rows of the model's prefill attention), the column sweep runs alone
+    fused = None
+    if cfg.dtype == "bf16" and cfg.d == 128:
+        win_out = torch.empty_like(q_win)
+        def timed(f, n=max(3, args.steps)):
+            f(); torch.cuda.synchronize()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for a, b in ev:
+                a.record(); f(); b.record()
+            torch.cuda.synchronize()
+            return float(np.median([a.elapsed_time(b) for a, b in ev]))
+        win_ms = timed(lambda: path.window_attn(q_win, k, v, sm, win_out))
+        col_ms = timed(lambda: path.score_from_stats(q_win, k, sm))
+        fused = {"window_attn_ms_per_batch": round(win_ms, 4), "score_from_stats_ms_per_batch": round(col_ms, 4),
+                 "window_attn_mfma_utilisation": round(score_flop / (win_ms * 1e-3) / MFMA_BF16_PEAK_FLOPS, 4)}
+        del win_out
+
     # ---- CacheHitRate (Def. 3.1) of the compressed cache against the first decode query, a quality figure
     # that needs no dataset: mean over (b, l, kv head) of |kept ∩ top-k of the decode query's attention| / k
     path.compress(q_win, k, v, sm)
@@ -195,6 +213,7 @@ def main() -> int:
                        "score_ms_per_batch": round(score_ms, 4),
                        "score_mfma_utilisation": None if mfma_util is None else round(mfma_util, 4),
                        "cache_hit_rate_mean": round(hit_rate_mean, 4),
+                       "fused_scoring_route": fused,
                        "budgets_request0": kk[0].tolist(), "input_generation_s": round(gen_s, 1)},
         "roofline": roofline,
     }

@@ -66,6 +66,16 @@ struct VStage {
     uint4 ra[NP], rb[NP];
     __device__ __forceinline__ void load(const bf16_t* vg, int key0, int m) {
         const int piece = threadIdx.x & 15;
+        if (key0 + kChunk <= m) {               // block-uniform: a whole chunk needs no per-key test
+#pragma unroll
+            for (int u = 0; u < NP; ++u) {
+                const int key = key0 + 2 * ((threadIdx.x >> 4) + (THREADS / 16) * u);
+                const uint4* src = reinterpret_cast<const uint4*>(vg + (size_t)key * kD + piece * 8);
+                ra[u] = src[0];
+                rb[u] = src[kD / 8];
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < NP; ++u) {
             const int key = key0 + 2 * ((threadIdx.x >> 4) + (THREADS / 16) * u);
@@ -99,6 +109,12 @@ struct VStage {
 __device__ __forceinline__ uint4 load_vt_frag(const uint8_t* sVt, int dt, int t, int s, int lane) {
     const int d = dt * 32 + (lane & 31);
     return *reinterpret_cast<const uint4*>(sVt + vt_granule_offset(d, t * 4 + s * 2 + (lane >> 5)));
+}
+
+// Maximum over the two lanes l and l ^ 32 (v_permlane32_swap: no trip through the LDS queue).
+__device__ __forceinline__ float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 template <int WAVES>
@@ -159,7 +175,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void window_attn_kernel(WinArgs a) {
             float tmax = v[0];
 #pragma unroll
             for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, v[i]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));      // both lane halves of a row use one max
+            tmax = max_across_halves(tmax);                    // both lane halves of a row use one max
             const float m_new = fmaxf(m_run, tmax * c);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;   // a row that has seen no key yet: all p = 0
             float p[16], zs = 0.f;

@@ -1,6 +1,8 @@
 """Sequencing of the hot path over the C-ABI calls: buffers and call order only, no arithmetic.
 
 After prefill:  vlc_score -> vlc_sparsity (finalise) -> vlc_allocate -> vlc_topk_compact.
+Fused route for the scores: vlc_window_attn (attention of the window rows + row statistics) ->
+vlc_score_from_stats (column sweep only).
 Every decode step: vlc_decode_attn over a layer range of the compressed cache.
 """
 from __future__ import annotations
@@ -47,6 +49,20 @@ class VLCachePath:
     def score(self, q_win, k, sm_scale) -> None:
         V.vlc_score(self.shape, q_win, k, sm_scale, self.p, self.scores, self.row_max, self.row_sum, self.nnz,
                     self.workspace)
+
+    def window_attn(self, q_win, k, v, sm_scale, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Attention of the window rows that also fills row_max / row_sum (bf16, d = 128): with it the
+        scores come from score_from_stats and the row-statistics sweep of score() is not run."""
+        if out is None:
+            out = torch.empty_like(q_win)
+        if getattr(self, "win_workspace", None) is None:
+            self.win_workspace = torch.empty(V.vlc_window_attn_workspace_bytes(self.shape), dtype=torch.uint8,
+                                             device=q_win.device)
+        V.vlc_window_attn(self.shape, q_win, k, v, sm_scale, out, self.row_max, self.row_sum, self.win_workspace)
+        return out
+
+    def score_from_stats(self, q_win, k, sm_scale) -> None:
+        V.vlc_score_from_stats(self.shape, q_win, k, sm_scale, self.p, self.row_max, self.row_sum, self.scores, self.nnz)
 
     def sparsity(self) -> None:
         V.vlc_sparsity(self.shape, None, None, None, None, self.p, self.nnz, self.gamma, None)

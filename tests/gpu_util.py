@@ -194,3 +194,34 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
     return path
 
 
+
+
+def check_window_attn(cfg, dev, requests_to_check, layers_to_check):
+    """vlc_window_attn + vlc_score_from_stats on an uploaded workload: the oracle on the listed
+    (request, layer) pairs, the score-mass property everywhere."""
+    import paper_2410_23317_amd as V
+    print(f"[case] window attention cfg={cfg.name} m={cfg.m} tau={cfg.tau} g={cfg.g}", flush=True)
+    shape = make_shape(cfg)
+    ws = torch.empty(V.vlc_window_attn_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(dev["q_win"])
+    row_max = torch.empty((cfg.B, cfg.L, cfg.Hq, cfg.tau), dtype=torch.float32, device="cuda")
+    row_sum = torch.empty_like(row_max)
+    scores = torch.empty((cfg.B, cfg.L, cfg.Hkv, cfg.m), dtype=torch.float32, device="cuda")
+    nnz = torch.empty((cfg.B, cfg.L, cfg.Hq), dtype=torch.int64, device="cuda")
+    V.vlc_window_attn(shape, dev["q_win"], dev["k"], dev["v"], dev["sm_scale"], out, row_max, row_sum, ws)
+    V.vlc_score_from_stats(shape, dev["q_win"], dev["k"], dev["sm_scale"], 0.01, row_max, row_sum, scores, nnz)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    np.testing.assert_allclose(scores.sum(-1).cpu().numpy(), cfg.g * cfg.tau, rtol=1e-4)
+    scales = W.sm_scale(cfg)
+    for b in requests_to_check:
+        for l in layers_to_check:
+            t = W.layer_inputs(cfg, b, l)
+            what = f"{cfg.name} b={b} l={l} window attention"
+            o_ref, M, Z = O.window_attention(t["q_win"], t["k"], t["v"], scales[l])
+            assert_close(out[b, l].float().cpu().numpy(), o_ref, atol=2e-2, rtol=1e-2, what=what + " out")
+            assert_close(row_max[b, l].cpu().numpy(), M, atol=2e-5, rtol=2e-6, what=what + " row_max")
+            assert_close(row_sum[b, l].cpu().numpy(), Z, atol=0, rtol=5e-5, what=what + " row_sum")
+            psi, _ = O.score_from_stats(t["q_win"], t["k"], scales[l], M, Z)
+            assert_close(scores[b, l].cpu().numpy(), psi, what=what + " scores", **SCORE_TOL)
+            check_nnz(nnz[b, l].cpu().numpy(), t["q_win"], t["k"], scales[l], 0.01, what + " nnz")

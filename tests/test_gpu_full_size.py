@@ -11,11 +11,13 @@ import workloads as W
 pytestmark = pytest.mark.gpu
 
 
-def _run(cid, alphas, reqs, lays, steps=2):
-    from gpu_util import run_and_check, upload
+def _run(cid, alphas, reqs, lays, steps=2, window_attn=False):
+    from gpu_util import check_window_attn, run_and_check, upload
     cfg = W.CONFIGS[cid]
     dev = upload(cfg)
     try:
+        if window_attn:
+            check_window_attn(cfg, dev, reqs[:1], lays[-1:])
         for alpha in alphas:
             path = run_and_check(cfg, alpha, steps, layers_to_check=lays, requests_to_check=reqs, dev=dev)
             del path
@@ -28,11 +30,11 @@ def _run(cid, alphas, reqs, lays, steps=2):
 
 
 def test_cfg2_7b_multi_image_batch():
-    _run(2, [(1, 10)], reqs=[0, 3], lays=[0, 17])
+    _run(2, [(1, 10)], reqs=[0, 3], lays=[0, 17], window_attn=True)
 
 
 def test_cfg3_34b_class_shape():
-    _run(3, [(1, 10)], reqs=[1], lays=[2, 59])
+    _run(3, [(1, 10)], reqs=[1], lays=[2, 59], window_attn=True)
 
 
 def test_cfg4_long_context_budget_sweep():

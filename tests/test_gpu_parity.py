@@ -147,3 +147,9 @@ def test_windows_longer_than_one_launch_of_row_blocks(kw):
 def test_cfg1_7b_shape_all_layers():
     cfg = W.CONFIGS[1]
     run_and_check(cfg, cfg.alphas[0], 4)
+
+
+def test_cfg1_7b_shape_window_attention():
+    from gpu_util import check_window_attn, upload
+    cfg = W.CONFIGS[1]
+    check_window_attn(cfg, upload(cfg), [0], [0, 13, 31])
