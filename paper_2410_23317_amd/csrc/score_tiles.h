@@ -52,6 +52,21 @@ struct KStage {
             r[u] = (key < m) ? *reinterpret_cast<const uint4*>(kg + (size_t)key * kD + piece * 8) : make_uint4(0, 0, 0, 0);
         }
     }
+    // The same in PARTS instalments (part P fetches pieces [P N / PARTS, (P + 1) N / PARTS)), for callers
+    // that spread the requests of a chunk over their compute phases.
+    template <int P, int PARTS>
+    __device__ __forceinline__ void load_part(const bf16_t* kg, int key0, int m) {
+        static_assert(N % PARTS == 0, "pieces per thread must divide evenly");
+        const bool whole = key0 + kChunk <= m;
+#pragma unroll
+        for (int u = P * (N / PARTS); u < (P + 1) * (N / PARTS); ++u) {
+            const int x = threadIdx.x + THREADS * u;
+            const int row = x >> 4, piece = x & 15;
+            const int key = key0 + row;
+            if (whole) r[u] = *reinterpret_cast<const uint4*>(kg + (size_t)key * kD + piece * 8);
+            else r[u] = (key < m) ? *reinterpret_cast<const uint4*>(kg + (size_t)key * kD + piece * 8) : make_uint4(0, 0, 0, 0);
+        }
+    }
     __device__ __forceinline__ void store(bf16_t* sK) const {
 #pragma unroll
         for (int u = 0; u < N; ++u) {

@@ -19,6 +19,8 @@
 // The key range is split across blocks as in the scoring sweeps; partial outputs (unnormalised,
 // with their max and sum) are merged by a second kernel, or written out directly when a KV group
 // has a single split.
+#include <type_traits>
+
 #include "common.h"
 #include "internal.h"
 #include "score_tiles.h"
@@ -82,6 +84,21 @@ struct VStage {
             const uint4* src = reinterpret_cast<const uint4*>(vg + (size_t)key * kD + piece * 8);
             ra[u] = (key < m) ? src[0] : make_uint4(0, 0, 0, 0);
             rb[u] = (key + 1 < m) ? src[kD / 8] : make_uint4(0, 0, 0, 0);
+        }
+    }
+    // The same in 4 instalments: the 2 NP requests of a thread, numbered 2 u + (second key of the pair).
+    template <int P>
+    __device__ __forceinline__ void load_part(const bf16_t* vg, int key0, int m) {
+        static_assert((2 * NP) % 4 == 0, "requests per thread must divide evenly");
+        const int piece = threadIdx.x & 15;
+        const bool whole = key0 + kChunk <= m;
+#pragma unroll
+        for (int j = P * (NP / 2); j < (P + 1) * (NP / 2); ++j) {
+            const int u = j >> 1, second = j & 1;
+            const int key = key0 + 2 * ((threadIdx.x >> 4) + (THREADS / 16) * u) + second;
+            const uint4* src = reinterpret_cast<const uint4*>(vg + (size_t)key * kD + piece * 8);
+            const uint4 val = (whole || key < m) ? *src : make_uint4(0, 0, 0, 0);
+            if (second) rb[u] = val; else ra[u] = val;
         }
     }
     __device__ __forceinline__ void store(uint8_t* sVt) const {
@@ -151,12 +168,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void window_attn_kernel(WinArgs a) {
         ks_.store(sK);
         vs_.store(sVt);
         __syncthreads();
-        if (kc + kChunk < k_end) { ks_.load(kg, kc + kChunk, mb); vs_.load(vg, kc + kChunk, mb); }
+        const bool next = kc + kChunk < k_end;                 // block-uniform
         const bool masked = kc + kChunk > mb - tb + 1;         // chunk reaches past the first window key
+        // In an 8-wave block the next chunk's global requests go out in four instalments, one per tile, so
+        // that the waves do not queue up behind the compute unit's one address path at the top of a chunk
+        // (measured: 940 cycles per chunk).  The 4-wave block has no registers for the unrolled form.
+        constexpr bool SPREAD = WAVES == 8;
+        if (next && (!SPREAD || !has_rows)) { ks_.load(kg, kc + kChunk, mb); vs_.load(vg, kc + kChunk, mb); }
         if (!has_rows) continue;
-#pragma unroll 1
-        for (int t = 0; t < kChunk / 32; ++t) {
-            if (kc + t * 32 >= k_end) break;
+        auto tile = [&](auto partc, int t) {
+            constexpr int part = decltype(partc)::value;
+            if constexpr (part >= 0) {
+                if (next) {
+                    ks_.template load_part<part, kChunk / 32>(kg, kc + kChunk, mb);
+                    vs_.template load_part<part>(vg, kc + kChunk, mb);
+                }
+            }
             uint4 kf[kKSteps];
             load_k_frags(sK, t, lane, kf);
             f32x16_t acc = {0};
@@ -201,6 +228,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void window_attn_kernel(WinArgs a) {
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
                     o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(load_vt_frag(sVt, dt, t, s, lane)), pf[s], o[dt], 0, 0, 0);
+        };
+        if constexpr (SPREAD) {
+            tile(std::integral_constant<int, 0>{}, 0);
+            if (kc + 32 < k_end) tile(std::integral_constant<int, 1>{}, 1);
+            if (kc + 64 < k_end) tile(std::integral_constant<int, 2>{}, 2);
+            if (kc + 96 < k_end) tile(std::integral_constant<int, 3>{}, 3);
+        } else {
+#pragma unroll 1
+            for (int t = 0; t < kChunk / 32 && kc + t * 32 < k_end; ++t) tile(std::integral_constant<int, -1>{}, t);
         }
     }
     if (!has_rows) return;
