@@ -28,7 +28,7 @@ struct MfmaArgs {
     const float* sm_scale;
     float2* part;            // [group][split][RP] partial (max, sum), exponent domain (log2)
     const float* row_max;    // natural-log domain, [B,L,Hq,tau]
-    const float* row_max_t;  // same in the exponent domain, or null
+    const float2* stat_p;    // per (group, padded row): (row max in the exponent domain, 1 / row sum), padding rows (+inf, 0); or null
     const float* row_sum;
     float* scores;           // may be null
     unsigned long long* nnz; // may be null
@@ -125,10 +125,12 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 0) void rowstats_mfma_
 }
 
 // Merge the per-split partials: one thread per (group, padded row).  Writes the natural-log row
-// max and the row sum in the caller's [B,L,Hq,tau] layout and the exponent-domain max for sweep 2.
+// max and the row sum in the caller's [B,L,Hq,tau] layout and, for sweep 2, the pair (exponent-domain
+// max, 1 / row sum) per padded row in the order the sweep's accumulators want them ((+inf, 0) for
+// padding rows, which then vanish from every sum).
 // The first n_clear threads also zero the per-head counters that sweep 2 adds into.
 __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
-                                           float* __restrict__ row_sum, float* __restrict__ row_max_t,
+                                           float* __restrict__ row_sum, float2* __restrict__ stat_p,
                                            int groups, int nsplit, int RP, int tauP, int tau, int g, int Hq, int Hkv,
                                            uint64_t* __restrict__ nnz_clear, size_t n_clear,
                                            const int32_t* __restrict__ lens, int L, int m) {
@@ -138,7 +140,7 @@ __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, floa
     const int r = (int)(x % RP), group = (int)(x / RP);
     const int hl = r / tauP, iw = r % tauP;
     const int hkv = group % Hkv, bl = group / Hkv;
-    if (hl >= g || iw >= request_len(lens, bl / L, m, tau).tau) return;
+    if (hl >= g || iw >= request_len(lens, bl / L, m, tau).tau) { stat_p[x] = make_float2(INFINITY, 0.f); return; }
     float M = -INFINITY;
     for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part[((size_t)group * nsplit + s) * RP + r].x);
     float Z = 0.f;
@@ -149,7 +151,7 @@ __global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, floa
     const size_t o = ((size_t)bl * Hq + (size_t)hkv * g + hl) * tau + iw;
     row_max[o] = M * kLn2;
     row_sum[o] = Z;
-    row_max_t[o] = M;
+    stat_p[x] = make_float2(M, 1.f / Z);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -177,14 +179,26 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         cnt[rb] = 0;
+        if (a.stat_p) {
+            // packed by the merge kernel: the 4 consecutive rows of accumulator slots 4 q .. 4 q + 3 are 32 bytes
+            const float2* sp = a.stat_p + (size_t)group * a.RP + (a.rb0 + wave * RB + rb) * 32 + 4 * (lane >> 5);
+            const bool have = (a.rb0 + wave * RB + rb) * 32 < a.RP;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 lo = have ? *reinterpret_cast<const float4*>(sp + 8 * q) : make_float4(INFINITY, 0.f, INFINITY, 0.f);
+                const float4 hi = have ? *reinterpret_cast<const float4*>(sp + 8 * q + 2) : make_float4(INFINITY, 0.f, INFINITY, 0.f);
+                mc[rb][4 * q] = lo.x; iz[rb][4 * q] = lo.y; mc[rb][4 * q + 1] = lo.z; iz[rb][4 * q + 1] = lo.w;
+                mc[rb][4 * q + 2] = hi.x; iz[rb][4 * q + 2] = hi.y; mc[rb][4 * q + 3] = hi.z; iz[rb][4 * q + 3] = hi.w;
+            }
+            continue;
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int r = (a.rb0 + wave * RB + rb) * 32 + acc_row(i, lane);
             const int hl = r / a.tauP, iw = r % a.tauP;
             const bool ok = hl < a.g && iw < tb;
             const size_t o = ((size_t)bl * a.Hq + (size_t)hkv * a.g + (ok ? hl : 0)) * a.tau + (ok ? iw : 0);
-            const float mt = a.row_max_t ? a.row_max_t[o] : a.row_max[o] * kLog2e;
-            mc[rb][i] = ok ? mt : INFINITY;
+            mc[rb][i] = ok ? a.row_max[o] * kLog2e : INFINITY;
             iz[rb][i] = (ok && a.row_sum) ? 1.f / a.row_sum[o] : 0.f;
         }
     }
@@ -290,7 +304,7 @@ MfmaArgs make_args(const ScoreArgs& a, const Plan& p) {
     const vlc_shape& s = a.s;
     m.q_win = (const bf16_t*)a.q_win; m.k = (const bf16_t*)a.k; m.sm_scale = a.sm_scale;
     m.part = (float2*)a.workspace;
-    m.row_max = a.row_max; m.row_sum = a.row_sum; m.row_max_t = nullptr;
+    m.row_max = a.row_max; m.row_sum = a.row_sum; m.stat_p = nullptr;
     m.scores = a.scores; m.nnz = (unsigned long long*)a.nnz;
     m.log2p = log2f(a.p);
     m.lens = s.lens;
@@ -315,6 +329,11 @@ size_t score_mfma_workspace_bytes(const vlc_shape& s) {
     return part_bytes(s, make_plan(s));
 }
 
+size_t score_mfma_stat_bytes(const vlc_shape& s) {
+    if (!score_mfma_supported(s)) return 0;
+    return ((size_t)s.B * s.L * s.Hkv * make_plan(s).RP * sizeof(float2) + 255) / 256 * 256;
+}
+
 // A launch covers up to 16 row blocks (32 padded window rows each) of every KV group; longer windows
 // take several launches over consecutive row-block ranges.  Block shape by row blocks in the launch:
 // up to 4 -> 4 waves, up to 8 -> 8 waves, else 8 waves x 2 row blocks (sweep 1) or 16 waves (sweep 2).
@@ -334,16 +353,16 @@ hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
     }
     const size_t n = (size_t)groups * p.RP;
     rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
-        m.part, a.row_max, a.row_sum, a.row_max_t, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv,
+        m.part, a.row_max, a.row_sum, (float2*)a.stat_p, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv,
         a.nnz, a.nnz ? (size_t)s.B * s.L * s.Hq : 0, s.lens, s.L, s.m);
     return hipGetLastError();
 }
 
-hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_row_max_t) {
+hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_stat_p) {
     const vlc_shape& s = a.s;
     const Plan p = make_plan(s);
     MfmaArgs m = make_args(a, p);
-    if (have_row_max_t) m.row_max_t = a.row_max_t;
+    if (have_stat_p) m.stat_p = (const float2*)a.stat_p;
     dim3 grid(p.nsplit, s.B * s.L * s.Hkv);
     const int total_rb = p.RP / 32;
     for (int rb0 = 0; rb0 < total_rb; rb0 += kMaxRowBlocksPerLaunch) {
