@@ -45,6 +45,7 @@ def _run(V, shape, q_win, k, v, sm, p=0.01):
     (403, 1, 1, 2, 2, 90, 90),        # window = whole prompt, shorter than one chunk
     (404, 1, 1, 4, 4, 129, 1),        # one window row, a chunk with one key
     (405, 2, 32, 8, 8, 200, 16),      # 512 KV groups: a single split, written without a merge
+    (406, 2, 32, 16, 8, 301, 160),    # single split and 10 row blocks: two launches, each writing its rows directly
 ])
 def test_window_attn_and_scores_from_its_statistics_match_the_oracle(cid, B, L, Hq, Hkv, m, tau):
     import paper_2410_23317_amd as V
