@@ -44,6 +44,7 @@ struct DecodeParams {
     int appended;            // appends before this call
     int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
     int prefetch;            // next tile's loads issued early (more registers, 2 blocks per CU)
+    int zigzag;              // tile order within a unit alternates between steps
     int kv_fp8;              // the cache rows are E4M3 codes with per-row scales
     float default_scale;
 };
@@ -429,15 +430,18 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
             if (more) issue_v(t0 + 4 * TK);
             __builtin_amdgcn_wave_barrier();
         };
-        // tiles of the unit are dealt round-robin to the 4 waves, so a partly filled unit keeps all of them busy
+        // tiles of the unit are dealt round-robin to the 4 waves, so a partly filled unit keeps all of them busy.
+        // A wave walks its tiles forwards on even steps and backwards on odd ones: a cache that is a little
+        // larger than an L2 then finds the tiles it touched last in the previous step first in this one.
         const int tw0 = key0 + wave * TK;
-        if (tw0 < len) { issue_k(tw0); issue_v(tw0); }
+        const int nt_w = tw0 < len ? min(NT, (len - tw0 + 4 * TK - 1) / (4 * TK)) : 0;     // tiles of this wave that hold slots
+        const bool rev = !PF && P.zigzag && ((P.appended + (appending ? 1 : 0)) & 1);
+        if (nt_w > 0) { const int t0 = tw0 + (rev ? nt_w - 1 : 0) * 4 * TK; issue_k(t0); issue_v(t0); }
 #pragma unroll 1
-        for (int t = 0; t < NT; ++t) {
-            const int t0 = tw0 + t * 4 * TK;
-            if (t0 >= len) break;               // wave-uniform
-            const bool more = PF && (t + 1 < NT) && (t0 + 4 * TK < len);
-            if (!PF && t > 0) { issue_k(t0); issue_v(t0); }
+        for (int i = 0; i < nt_w; ++i) {
+            const int t0 = tw0 + (rev ? nt_w - 1 - i : i) * 4 * TK;
+            const bool more = PF && (i + 1 < nt_w);
+            if (!PF && i > 0) { issue_k(t0); issue_v(t0); }
             const bool full = (t0 + TK <= len);
             if (full) tile_body(std::true_type{}, t0, more); else tile_body(std::false_type{}, t0, more);
         }
@@ -625,6 +629,7 @@ hipError_t launch_decode(const DecodeArgs& a) {
     P.default_scale = 1.0f / sqrtf((float)s.d);
     P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knobs
     P.prefetch = env_int("VLC_DECODE_PREFETCH", 0);
+    P.zigzag = env_int("VLC_DECODE_ZIGZAG", 1);
     P.kv_fp8 = c.kv_fp8 ? 1 : 0;
     const int rows = a.n_layers * s.B * s.Hkv;
     // Upper bound on the block-units of the layer range: every row at the full prompt length, and
