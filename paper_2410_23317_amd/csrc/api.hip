@@ -254,7 +254,7 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     lay->scratch_off = off;
     plan->items_off = off;        off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
     plan->items2_off = off;       off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
-    plan->layer_start_off = off;  off = align_up(off + (size_t)(s->L + 1) * sizeof(int32_t), 256);
+    plan->layer_start_off = off;  off = align_up(off + (size_t)(s->L + 2) * sizeof(int32_t), 256);
     plan->row_first_off = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
     plan->partials_off = off;     off = align_up(off + (size_t)plan->max_items * g * (s->d + 2) * sizeof(float), 256);
     plan->counters_off = off;     off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);

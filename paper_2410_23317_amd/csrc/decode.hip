@@ -44,7 +44,8 @@ struct DecodeParams {
     int appended;            // appends before this call
     int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
     int prefetch;            // next tile's loads issued early (more registers, 2 blocks per CU)
-    int zigzag;              // tile order within a unit alternates between steps
+    int zigzag;              // 1: tile order within a unit alternates between steps; 2: also the walk over the full units
+    int rev_full;            // size-class order only: walk the full units backwards in this launch
     int kv_fp8;              // the cache rows are E4M3 codes with per-row scales
     float default_scale;
 };
@@ -213,6 +214,10 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
     // that starts at layer 0 starts at unit 0, so the unit record does not wait for the range lookup
     // (the grid never exceeds the list's capacity, so a surplus block reads an unused record).
     int w = blockIdx.x;
+    if (P.rev_full) {                           // size-class order, odd step: the full units are walked backwards, so that
+        const int nf = min(P.dev.layer_item_start[P.L + 1], (int)gridDim.x);   // what the memory-side cache kept of the last step comes first
+        if (w < nf) w = nf - 1 - w;
+    }
     if (P.layer_begin != 0) {
         w += P.dev.layer_item_start[P.layer_begin];
         if (w >= P.dev.layer_item_start[P.layer_begin + P.n_layers]) return;
@@ -629,7 +634,8 @@ hipError_t launch_decode(const DecodeArgs& a) {
     P.default_scale = 1.0f / sqrtf((float)s.d);
     P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knobs
     P.prefetch = env_int("VLC_DECODE_PREFETCH", 0);
-    P.zigzag = env_int("VLC_DECODE_ZIGZAG", 1);
+    P.zigzag = env_int("VLC_DECODE_ZIGZAG", 2);                           // tuning knob: 0 off, 1 tiles only
+    P.rev_full = (P.items == c.dev.items_by_size && P.zigzag > 1 && ((a.appended + (a.k_new ? 1 : 0)) & 1)) ? 1 : 0;
     P.kv_fp8 = c.kv_fp8 ? 1 : 0;
     const int rows = a.n_layers * s.B * s.Hkv;
     // Upper bound on the block-units of the layer range: every row at the full prompt length, and

@@ -39,7 +39,7 @@ struct CacheDev {                      // device pointers into the caller's aren
     int32_t* idx;
     WorkItem* items;                   // [max_items], layer-major order
     WorkItem* items_by_size;           // [max_items], the same units by size class
-    int32_t* layer_item_start;         // [L+1]
+    int32_t* layer_item_start;         // [L+2]: first unit of each layer, the number of units, the number of full units
     int32_t* row_item_first;           // [B*L*Hkv]
     float* partials;                   // [max_items][g][d + 2]
     int32_t* counters;                 // [B*L*Hkv]

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
                 set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
                 sBad = 1;
             }
-            for (int l = tid; l <= L; l += 256) dev.layer_item_start[l] = 0;
+            for (int l = tid; l <= L + 1; l += 256) dev.layer_item_start[l] = 0;
         } else {
             int64_t acc = sScan[tid] - run, acc2 = sScan2[tid] - run2;
             for (int y = y0; y < y1; ++y) {
@@ -120,6 +120,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
     }
     if (sBad) return;
     const int n_full = sTotals[0], n_part = sTotals[1];
+    if (tid == 0) dev.layer_item_start[L + 1] = n_full;         // decode reverses the walk over the full units on odd steps
     for (int x = tid; x < BL * Hkv; x += blockDim.x) {
         const int h = x % Hkv, bl = x / Hkv, b = bl / L, l = bl % L;
         const int kk = sKept[bl];
