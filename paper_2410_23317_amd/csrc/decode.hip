@@ -216,7 +216,8 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
     int w = blockIdx.x;
     if (P.rev_full) {                           // size-class order, odd step: the full units are walked backwards, so that
         const int nf = min(P.dev.layer_item_start[P.L + 1], (int)gridDim.x);   // what the memory-side cache kept of the last step comes first
-        if (w < nf) w = nf - 1 - w;
+        const int nf8 = nf & ~7;                // whole groups of 8 change places, so a unit stays on its XCD (and its L2)
+        if (w < nf8) w = nf8 - 8 - (w & ~7) + (w & 7);
     }
     if (P.layer_begin != 0) {
         w += P.dev.layer_item_start[P.layer_begin];
