@@ -334,10 +334,13 @@ def test_whole_path_replays_from_a_hip_graph():
 
 @pytest.mark.parametrize("env", [{"VLC_UNIT_SLOTS": "128"}, {"VLC_UNIT_SLOTS": "128", "VLC_DECODE_MERGE": "2"},
                                  {"VLC_UNIT_SLOTS": "256"}, {"VLC_UNIT_SLOTS": "128", "VLC_DECODE_ORDER": "2"},
-                                 {"VLC_UNIT_SLOTS": "256", "VLC_DECODE_ORDER": "2", "VLC_DECODE_MERGE": "2"}])
+                                 {"VLC_UNIT_SLOTS": "256", "VLC_DECODE_ORDER": "2", "VLC_DECODE_MERGE": "2"},
+                                 {"VLC_UNIT_SLOTS": "512", "VLC_DECODE_ORDER": "2"}, {"VLC_UNIT_SLOTS": "512", "VLC_DECODE_ZIGZAG": "0"},
+                                 {"VLC_UNIT_SLOTS": "256", "VLC_DECODE_ZIGZAG": "1", "VLC_DECODE_ORDER": "2"}])
 def test_decode_merges_across_units(env):
     """Rows longer than one block-unit: partial results merged in-kernel (device-scope counter) or by the
-    second kernel, with the work list walked layer-major or by size class, all against the oracle."""
+    second kernel, with the work list walked layer-major or by size class, tiles and full units walked
+    forwards and backwards on alternate steps or always forwards, all against the oracle."""
     from gpu_util import run_and_check
     cfg = _small_cfg(cid=85, m=1300, n_visual=1200, L=2, B=2, alphas=((1, 2),), Hq=14, Hkv=2)
     old = {k: os.environ.get(k) for k in env}
