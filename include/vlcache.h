@@ -22,6 +22,11 @@
  *     small for the budgets) set a sticky flag inside the cache; the offending rows are skipped
  *     without touching memory, and vlc_cache_status reports the flag.
  *   - Query head h reads key/value head h / g (consecutive query heads share a KV head).
+ *   - A vlc_cache owns device scratch (partial results, counters) and host-side append counts:
+ *     calls on one cache come from one thread at a time, on one stream or on streams the caller
+ *     orders; calls that overlap on the device race.  Different caches are independent.  The
+ *     scoring calls keep their intermediates in the caller's workspace: calls that may overlap on
+ *     the device need workspaces of their own.
  */
 #ifndef VLCACHE_H
 #define VLCACHE_H
