@@ -5,6 +5,8 @@
 //   select : radix-select of the k-th largest score over keys held in registers, then an ordered
 //            compaction that emits the kept positions ascending (ties to the lower position)
 //   gather : one block per work-list unit streams the kept rows of K and V into the slabs
+#include <stdlib.h>
+
 #include "common.h"
 #include "internal.h"
 
@@ -380,24 +382,27 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     }
 }
 
-// One block per unit of the decode work list: up to `unit_slots` kept rows of one (request, layer,
-// KV head) row.  The grid is the list's capacity, so it follows the budgets that fit the arena rather
-// than rows * m, and surplus blocks leave after two loads.  Each lane moves 16 bytes of one K row and
+// `parts` blocks per unit of the decode work list (up to `unit_slots` kept rows of one (request, layer,
+// KV head) row), each moving an equal share of it.  The grid is a multiple of the list's capacity, so it
+// follows the budgets that fit the arena rather than rows * m, and surplus blocks leave after two loads.  Each lane moves 16 bytes of one K row and
 // one V row per pass; the position of the next row is fetched before the stores are issued.  More
 // rows in flight per lane measured slower on every shape (the gathered reads are 256-byte pieces at
 // random DRAM pages; eight blocks per CU already keep enough of them outstanding).
 template <int ROWBYTES>
 __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_full, const char* __restrict__ v_full,
                                                      CacheDev dev, int L, int Hkv, int m, int T_max, int unit_slots,
-                                                     int elem_bytes) {
+                                                     int elem_bytes, int parts) {
     constexpr int LPR = ROWBYTES / 16;          // lanes per row
     constexpr int RPB = 256 / LPR;              // rows per block pass
-    const int w = blockIdx.x;
+    const int w = blockIdx.x / parts, part = blockIdx.x % parts;
     const WorkItem it = dev.items[w];           // the grid never exceeds the list's capacity
     if (w >= dev.layer_item_start[L]) return;
     const int kk = it.kept, key0 = it.key0;
     if (kk == 0 || key0 >= kk) return;          // rejected row, or a unit reserved for appends
-    const int r_end = min(kk, key0 + unit_slots);
+    const int span = unit_slots / parts;        // a block moves one of `parts` equal shares of the unit
+    const int r_begin = key0 + part * span;
+    const int r_end = min(kk, r_begin + span);
+    if (r_begin >= r_end) return;
     const int cap = kk + T_max;
     uint4* kd = reinterpret_cast<uint4*>(dev.kv + it.kbase * elem_bytes);
     uint4* vd = kd + (int64_t)Hkv * cap * LPR;
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_
     const uint4* vs = reinterpret_cast<const uint4*>(v_full + (size_t)it.row_abs * m * ROWBYTES);
     const int32_t* idx = dev.idx + it.idx_base;
     const int c = threadIdx.x % LPR, sub = threadIdx.x / LPR;
-    int r = key0 + sub;
+    int r = r_begin + sub;
     int32_t jn = r < r_end ? idx[r] : 0;
     for (; r < r_end; r += RPB) {
         const uint4 a = ks[(int64_t)jn * LPR + c];
@@ -483,9 +488,15 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
         else gather_fp8_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots);
         return hipGetLastError();
     }
-    if (rowbytes == 128) gather_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
-    else if (rowbytes == 256) gather_kernel<256><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
-    else gather_kernel<512><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es);
+    // Four blocks share a unit: more, shorter chains of dependent passes in flight (measured 2-3 % on the
+    // whole compaction against one block per unit, on the smallest and on the largest shape alike).
+    const char* knob = getenv("VLC_GATHER_PARTS");              // tuning knob: 1, 2 or 4
+    const int kp = knob ? atoi(knob) : 4;
+    const int parts = (kp == 1 || kp == 2) ? kp : 4;
+    const unsigned g2 = grid * (unsigned)parts;
+    if (rowbytes == 128) gather_kernel<128><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es, parts);
+    else if (rowbytes == 256) gather_kernel<256><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es, parts);
+    else gather_kernel<512><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es, parts);
     return hipGetLastError();
 }
 
