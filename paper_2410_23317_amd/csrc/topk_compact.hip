@@ -488,11 +488,11 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
         else gather_fp8_kernel<128><<<grid, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots);
         return hipGetLastError();
     }
-    // Four blocks share a unit: more, shorter chains of dependent passes in flight (measured 2-3 % on the
-    // whole compaction against one block per unit, on the smallest and on the largest shape alike).
-    const char* knob = getenv("VLC_GATHER_PARTS");              // tuning knob: 1, 2 or 4
-    const int kp = knob ? atoi(knob) : 4;
-    const int parts = (kp == 1 || kp == 2) ? kp : 4;
+    // Eight blocks share a unit: more, shorter chains of dependent passes in flight (measured 3-7 % on the
+    // whole compaction against one block per unit).
+    const char* knob = getenv("VLC_GATHER_PARTS");              // tuning knob: 1, 2, 4 or 8
+    const int kp = knob ? atoi(knob) : 8;
+    const int parts = (kp == 1 || kp == 2 || kp == 4) ? kp : 8;
     const unsigned g2 = grid * (unsigned)parts;
     if (rowbytes == 128) gather_kernel<128><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es, parts);
     else if (rowbytes == 256) gather_kernel<256><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, c.unit_slots, es, parts);
