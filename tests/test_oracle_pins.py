@@ -158,6 +158,17 @@ def test_alloc_integer_worked_examples():
     # upper clip: alpha = 1 and one dense layer
     k, _ = O.allocate(np.array([[900], [100]]), 1000, 1, 1)
     assert list(k) == [1000, 200]
+    # equal sparsity, odd budget: 2 layers, m = 101, alpha = 1/2 -> 101 tokens, quotas 50 + 50, the token
+    # left over goes to the layer with the larger remainder, and among equal remainders to the lower layer
+    k, _ = O.allocate(np.array([[7], [7]]), 101, 1, 2)
+    assert list(k) == [51, 50]
+    # three layers in proportion 1 : 2 : 4 of 70 tokens: exact quotas 10, 20, 40, nothing left over
+    k, _ = O.allocate(np.array([[3], [6], [12]]), 100, 7, 30)
+    assert list(k) == [10, 20, 40]
+    # remainders decide before layer order: n = (1, 1, 2), 10 tokens -> quotas 2.5, 2.5, 5 -> floors 2, 2, 5 and
+    # one token left, equal remainders on layers 0 and 1 -> layer 0
+    k, _ = O.allocate(np.array([[1], [1], [2]]), 100, 1, 30)
+    assert list(k) == [3, 2, 5]
 
 
 def test_alloc_invariants_random():
@@ -276,6 +287,10 @@ def test_cache_hit_rate_definition():
         order = sorted(range(m), key=lambda j: (-star[j], j))[:k]
         hits = len(set(order) & set(kept.tolist()))
         assert O.cache_hit_rate(star, kept, k) == (hits, hits / k)
+    # the denominator is |S*| = k (Def. 3.1), not the size of the preserved set: a policy that keeps twice as
+    # many positions, all of S* among them, scores 1
+    assert O.cache_hit_rate(star, np.concatenate([best, rest]), k) == (k, 1.0)
+    assert O.cache_hit_rate(star, best[:5], k) == (5, 5 / k)
     # ties at the cut go to the lower position
     tied = np.array([1.0, 0.5, 0.5, 0.5, 0.0])
     assert O.cache_hit_rate(tied, np.array([0, 1]), 2) == (2, 1.0)
