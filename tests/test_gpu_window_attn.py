@@ -158,3 +158,28 @@ def test_score_from_stats_takes_the_statistics_as_given_fp32_storage():
         check_nnz(nnz[0, l].cpu().numpy(), host[l]["q_win"], host[l]["k"], scales[l], 0.01, f"l={l} nnz")
     with pytest.raises(V.VlcError):
         V.vlc_window_attn_workspace_bytes(shape)             # the attention kernel is built for bf16, d = 128
+
+
+def test_the_output_tolerance_notices_a_wrong_oracle():
+    """The comparison itself is checked on one case: an oracle with a planted mistake (values shifted by one
+    key, or the window placed one position early) must fall outside the tolerance the tests above use."""
+    import paper_2410_23317_amd as V
+    cfg = _cfg(440, 1, 1, 4, 2, 500, 32)
+    dt = torch.bfloat16
+    t = W.layer_inputs(cfg, 0, 0)
+    q_win = torch.from_numpy(t["q_win"]).to(dt).cuda()[None, None].contiguous()
+    k = torch.from_numpy(t["k"]).to(dt).cuda()[None, None].contiguous()
+    v = torch.from_numpy(t["v"]).to(dt).cuda()[None, None].contiguous()
+    scales = W.sm_scale(cfg)
+    shape = V.make_shape(1, 1, 4, 2, 128, 500, 32, "bf16")
+    out, row_max, row_sum, scores, nnz = _run(V, shape, q_win, k, v, torch.from_numpy(scales).cuda())
+    got = out[0, 0].float().cpu().numpy()
+    good, M, Z = O.window_attention(t["q_win"], t["k"], t["v"], scales[0])
+    assert_close(got, good, what="as is", **OUT_TOL)
+    shifted, _, _ = O.window_attention(t["q_win"], t["k"], np.roll(t["v"], 1, axis=1), scales[0])
+    with pytest.raises(AssertionError):
+        assert_close(got, shifted, what="values shifted by one key", **OUT_TOL)
+    _, _, Z_e = O.window_attention(t["q_win"], t["k"][:, :-1], t["v"][:, :-1], scales[0])   # every row sees one key fewer
+    assert_close(row_sum[0, 0].cpu().numpy(), Z, atol=0, rtol=5e-5, what="as is")
+    with pytest.raises(AssertionError):
+        assert_close(row_sum[0, 0].cpu().numpy(), Z_e, atol=0, rtol=5e-5, what="window one position early")
