@@ -353,3 +353,19 @@ def test_decode_merges_across_units(env):
                 os.environ.pop(k, None)
             else:
                 os.environ[k] = v
+
+
+@pytest.mark.parametrize("attr,mutant", [("causal_valid", "_strict_mask"), ("logits", "_logits_interleaved_heads"),
+                                         ("score", "_score_mean_over_rows"), ("decode_attn", "_decode_without_scale"),
+                                         ("k_min", "_k_min_floor")])
+def test_the_parity_harness_notices_a_wrong_oracle(monkeypatch, attr, mutant):
+    """The comparison of the whole path is itself checked: with one mistake planted in the oracle (on the CPU) the
+    same harness that passes above must report a difference."""
+    import test_oracle_mutants as Mu
+    from gpu_util import run_and_check
+    from oracle import vlcache_oracle as O
+    cfg = _small_cfg(cid=87, L=3, alphas=((1, 100),))       # m = 777 and alpha = 1 %: the lower clip (8 tokens) binds
+    run_and_check(cfg, (1, 100), 2)
+    monkeypatch.setattr(O, attr, getattr(Mu, mutant))
+    with pytest.raises((AssertionError, ValueError)):
+        run_and_check(cfg, (1, 100), 2)
