@@ -54,8 +54,8 @@ double region_size(const vlc_shape& s) {
 }
 
 // Workspace layout: [partial row statistics][3 arrays of B L Hq tau floats: two hold the row max and row sum of a
-// standalone vlc_sparsity sweep][packed statistics of the matrix-core column sweep]
-struct WsPlan { size_t part, stats, packed, total; bool mfma; };
+// standalone vlc_sparsity sweep]
+struct WsPlan { size_t part, stats, total; bool mfma; };
 
 WsPlan ws_plan(const vlc_shape& s) {
     WsPlan w;
@@ -64,8 +64,7 @@ WsPlan ws_plan(const vlc_shape& s) {
     const size_t a = vlc::score_simple_workspace_bytes(s), b = vlc::score_mfma_workspace_bytes(s);
     w.part = align_up(a > b ? a : b, 256);
     w.stats = align_up((size_t)s.B * s.L * s.Hq * s.tau * sizeof(float), 256);
-    w.packed = vlc::score_mfma_stat_bytes(s);
-    w.total = w.part + 3 * w.stats + w.packed;
+    w.total = w.part + 3 * w.stats;
     return w;
 }
 
@@ -74,15 +73,14 @@ vlc::ScoreArgs score_args(const vlc_shape* s, const void* q_win, const void* k, 
     vlc::ScoreArgs a;
     a.s = *s; a.q_win = q_win; a.k = k; a.sm_scale = sm_scale; a.p = p; a.scores = scores;
     a.row_max = row_max; a.row_sum = row_sum; a.nnz = nnz; a.workspace = ws; a.stream = (hipStream_t)st;
-    { const WsPlan w = ws_plan(*s); a.stat_p = (char*)ws + w.part + 3 * w.stats; }
     return a;
 }
 
 hipError_t run_rowstats(const vlc::ScoreArgs& a, bool mfma) {
     return mfma ? vlc::launch_rowstats_mfma(a) : vlc::launch_rowstats_simple(a);
 }
-hipError_t run_colsweep(const vlc::ScoreArgs& a, bool mfma, bool have_stat_p) {
-    return mfma ? vlc::launch_colsweep_mfma(a, have_stat_p) : vlc::launch_colsweep_simple(a);
+hipError_t run_colsweep(const vlc::ScoreArgs& a, bool mfma, bool after_rowstats) {
+    return mfma ? vlc::launch_colsweep_mfma(a, after_rowstats) : vlc::launch_colsweep_simple(a);
 }
 
 }  // namespace
@@ -110,7 +108,7 @@ vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k, c
     const bool mfma = ws_plan(*shape).mfma;
     hipError_t e = run_rowstats(a, mfma);
     if (e != hipSuccess) return hip_fail(e, "vlc_score row statistics");
-    e = run_colsweep(a, mfma, true);              // the counters were zeroed by the row-statistics merge
+    e = run_colsweep(a, mfma, true);              // the counters were zeroed by the row-statistics sweep
     if (e != hipSuccess) return hip_fail(e, "vlc_score column sweep");
     return VLC_OK;
 }
@@ -190,7 +188,7 @@ vlc_status vlc_score_from_stats(const vlc_shape* shape, const void* q_win, const
     if (nnz && !(p > 0.f && p < 1.f)) return fail(VLC_ERR_INVALID_ARG, "vlc_score_from_stats: p = %g is outside (0, 1)", p);
     vlc::ScoreArgs a;
     a.s = *shape; a.q_win = q_win; a.k = k; a.sm_scale = sm_scale; a.p = nnz ? p : 0.5f; a.scores = scores;
-    a.row_max = const_cast<float*>(row_max); a.row_sum = const_cast<float*>(row_sum); a.stat_p = nullptr;
+    a.row_max = const_cast<float*>(row_max); a.row_sum = const_cast<float*>(row_sum);
     a.nnz = nnz; a.workspace = nullptr; a.stream = (hipStream_t)stream;
     hipError_t e = hipSuccess;
     if (nnz) e = vlc::launch_fill_u64(nnz, (size_t)shape->B * shape->L * shape->Hq, 0, a.stream);

@@ -77,7 +77,6 @@ struct ScoreArgs {
     float* scores;              // null: count only
     float* row_max;
     float* row_sum;
-    void* stat_p;               // scratch, matrix-core path: (exponent-domain row max, 1 / row sum) per padded window row
     uint64_t* nnz;              // null: no counting
     void* workspace;
     hipStream_t stream;
@@ -87,9 +86,8 @@ hipError_t launch_rowstats_simple(const ScoreArgs& a);     // fills row_max, row
 hipError_t launch_colsweep_simple(const ScoreArgs& a);     // scores and/or nnz from row_max,row_sum
 bool score_mfma_supported(const vlc_shape& s);            // bf16, d = 128
 size_t score_mfma_workspace_bytes(const vlc_shape& s);
-size_t score_mfma_stat_bytes(const vlc_shape& s);         // bytes of ScoreArgs::stat_p
-hipError_t launch_rowstats_mfma(const ScoreArgs& a);       // fills row_max, row_sum, stat_p; zeroes nnz if given
-hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_stat_p);
+hipError_t launch_rowstats_mfma(const ScoreArgs& a);       // leaves per-split partial statistics in the workspace; zeroes nnz if given
+hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool merge_partials);   // merge_partials: statistics come from the sweep just run (row_max, row_sum are then outputs)
 hipError_t launch_fill_u64(uint64_t* p, size_t n, uint64_t v, hipStream_t st);
 hipError_t launch_gamma(const vlc_shape& s, const uint64_t* nnz, float* gamma, hipStream_t st);
 

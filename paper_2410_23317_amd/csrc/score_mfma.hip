@@ -6,7 +6,8 @@
 //   sweep 1 (row statistics) computes S^T = K Q'^T tile by tile, so that the 16 values a lane holds
 //           belong to ONE query row: running max and sum stay in the lane, with one rescale per
 //           32-key tile instead of one per element;
-//   sweep 2 (column sums + ThresholdFilter counts) computes S = Q' K^T, so that a lane holds 16
+//   sweep 2 (column sums + ThresholdFilter counts) first merges sweep 1's per-split statistics for its own rows,
+//           then computes S = Q' K^T, so that a lane holds 16
 //           query rows of ONE key: the sum over the window rows of Sec. 3.2 is in-lane too, and the
 //           Eq. 1 test is one compare on the exponent argument.
 // Q' fragments of a block's rows live in registers for the whole sweep; K streams through LDS in
@@ -28,7 +29,9 @@ struct MfmaArgs {
     const float* sm_scale;
     float2* part;            // [group][split][RP] partial (max, sum), exponent domain (log2)
     const float* row_max;    // natural-log domain, [B,L,Hq,tau]
-    const float2* stat_p;    // per (group, padded row): (row max in the exponent domain, 1 / row sum), padding rows (+inf, 0); or null
+    const float2* part_in;   // sweep 2: partials of sweep 1 to merge in the prologue, or null (statistics given)
+    float* row_max_out;      // sweep 2 with part_in: where the merged statistics go ([B,L,Hq,tau]; either may be null)
+    float* row_sum_out;
     const float* row_sum;
     float* scores;           // may be null
     unsigned long long* nnz; // may be null
@@ -55,6 +58,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 0) void rowstats_mfma_
     const int k_begin = split * a.keys_per_split;
     const int k_end = min(mb, k_begin + a.keys_per_split);
 
+    if (a.nnz && split == 0 && a.rb0 == 0 && (int)threadIdx.x < a.g)
+        a.nnz[(size_t)bl * a.Hq + (size_t)hkv * a.g + threadIdx.x] = 0;      // sweep 2 adds into these
     uint4 qf[RB][kKSteps];
     load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, tb, qf);
     // this lane's query row per row block, and the last key it may see (causal mask of Alg. 1)
@@ -124,36 +129,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 0) void rowstats_mfma_
     }
 }
 
-// Merge the per-split partials: one thread per (group, padded row).  Writes the natural-log row
-// max and the row sum in the caller's [B,L,Hq,tau] layout and, for sweep 2, the pair (exponent-domain
-// max, 1 / row sum) per padded row in the order the sweep's accumulators want them ((+inf, 0) for
-// padding rows, which then vanish from every sum).
-// The first n_clear threads also zero the per-head counters that sweep 2 adds into.
-__global__ void rowstats_merge_mfma_kernel(const float2* __restrict__ part, float* __restrict__ row_max,
-                                           float* __restrict__ row_sum, float2* __restrict__ stat_p,
-                                           int groups, int nsplit, int RP, int tauP, int tau, int g, int Hq, int Hkv,
-                                           uint64_t* __restrict__ nnz_clear, size_t n_clear,
-                                           const int32_t* __restrict__ lens, int L, int m) {
-    const size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (x < n_clear) nnz_clear[x] = 0;
-    if (x >= (size_t)groups * RP) return;
-    const int r = (int)(x % RP), group = (int)(x / RP);
-    const int hl = r / tauP, iw = r % tauP;
-    const int hkv = group % Hkv, bl = group / Hkv;
-    if (hl >= g || iw >= request_len(lens, bl / L, m, tau).tau) { stat_p[x] = make_float2(INFINITY, 0.f); return; }
-    float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, part[((size_t)group * nsplit + s) * RP + r].x);
-    float Z = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float2 p = part[((size_t)group * nsplit + s) * RP + r];
-        if (p.x > -INFINITY) Z += p.y * exp2_fast(p.x - M);
-    }
-    const size_t o = ((size_t)bl * Hq + (size_t)hkv * g + hl) * tau + iw;
-    row_max[o] = M * kLn2;
-    row_sum[o] = Z;
-    stat_p[x] = make_float2(M, 1.f / Z);
-}
-
 // ------------------------------------------------------------------------------------------------
 // Sweep 2: column sums of the softmax over all window rows of the KV group, and per-head counts.
 template <int WAVES, int RB>
@@ -176,17 +151,42 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     // per accumulator slot: exponent offset (+inf for padded rows) and 1 / row sum
     float mc[RB][16], iz[RB][16];
     uint32_t cnt[RB];
+    __shared__ __align__(16) float2 sStat[WAVES * RB * 32];
+    if (a.part_in) {
+        // the partial statistics of sweep 1's key splits are merged here, one thread per row of the block; the
+        // block of the first split also writes the row maximum and sum the caller asked for
+        for (int t = threadIdx.x; t < WAVES * RB * 32; t += THREADS) {
+            const int r = a.rb0 * 32 + t;
+            float2 st = make_float2(INFINITY, 0.f);
+            const int hl = r / a.tauP, iw = r % a.tauP;
+            if (r < a.RP && hl < a.g && iw < tb) {
+                float M = -INFINITY;
+                for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, a.part_in[((size_t)group * a.nsplit + sp) * a.RP + r].x);
+                float Z = 0.f;
+                for (int sp = 0; sp < a.nsplit; ++sp) {
+                    const float2 pp = a.part_in[((size_t)group * a.nsplit + sp) * a.RP + r];
+                    if (pp.x > -INFINITY) Z += pp.y * exp2_fast(pp.x - M);
+                }
+                st = make_float2(M, 1.f / Z);
+                if (split == 0) {                  // either output may be absent (a count-only sweep keeps no row sums)
+                    const size_t o = ((size_t)bl * a.Hq + (size_t)hkv * a.g + hl) * a.tau + iw;
+                    if (a.row_max_out) a.row_max_out[o] = M * kLn2;
+                    if (a.row_sum_out) a.row_sum_out[o] = Z;
+                }
+            }
+            sStat[t] = st;
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         cnt[rb] = 0;
-        if (a.stat_p) {
-            // packed by the merge kernel: the 4 consecutive rows of accumulator slots 4 q .. 4 q + 3 are 32 bytes
-            const float2* sp = a.stat_p + (size_t)group * a.RP + (a.rb0 + wave * RB + rb) * 32 + 4 * (lane >> 5);
-            const bool have = (a.rb0 + wave * RB + rb) * 32 < a.RP;
+        if (a.part_in) {
+            const float2* sp = sStat + (wave * RB + rb) * 32 + 4 * (lane >> 5);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float4 lo = have ? *reinterpret_cast<const float4*>(sp + 8 * q) : make_float4(INFINITY, 0.f, INFINITY, 0.f);
-                const float4 hi = have ? *reinterpret_cast<const float4*>(sp + 8 * q + 2) : make_float4(INFINITY, 0.f, INFINITY, 0.f);
+                const float4 lo = *reinterpret_cast<const float4*>(sp + 8 * q);
+                const float4 hi = *reinterpret_cast<const float4*>(sp + 8 * q + 2);
                 mc[rb][4 * q] = lo.x; iz[rb][4 * q] = lo.y; mc[rb][4 * q + 1] = lo.z; iz[rb][4 * q + 1] = lo.w;
                 mc[rb][4 * q + 2] = hi.x; iz[rb][4 * q + 2] = hi.y; mc[rb][4 * q + 3] = hi.z; iz[rb][4 * q + 3] = hi.w;
             }
@@ -304,7 +304,8 @@ MfmaArgs make_args(const ScoreArgs& a, const Plan& p) {
     const vlc_shape& s = a.s;
     m.q_win = (const bf16_t*)a.q_win; m.k = (const bf16_t*)a.k; m.sm_scale = a.sm_scale;
     m.part = (float2*)a.workspace;
-    m.row_max = a.row_max; m.row_sum = a.row_sum; m.stat_p = nullptr;
+    m.row_max = a.row_max; m.row_sum = a.row_sum;
+    m.part_in = nullptr; m.row_max_out = a.row_max; m.row_sum_out = a.row_sum;
     m.scores = a.scores; m.nnz = (unsigned long long*)a.nnz;
     m.log2p = log2f(a.p);
     m.lens = s.lens;
@@ -329,11 +330,6 @@ size_t score_mfma_workspace_bytes(const vlc_shape& s) {
     return part_bytes(s, make_plan(s));
 }
 
-size_t score_mfma_stat_bytes(const vlc_shape& s) {
-    if (!score_mfma_supported(s)) return 0;
-    return ((size_t)s.B * s.L * s.Hkv * make_plan(s).RP * sizeof(float2) + 255) / 256 * 256;
-}
-
 // A launch covers up to 16 row blocks (32 padded window rows each) of every KV group; longer windows
 // take several launches over consecutive row-block ranges.  Block shape by row blocks in the launch:
 // up to 4 -> 4 waves, up to 8 -> 8 waves, else 8 waves x 2 row blocks (sweep 1) or 16 waves (sweep 2).
@@ -351,18 +347,14 @@ hipError_t launch_rowstats_mfma(const ScoreArgs& a) {
         else if (nrb <= 8) rowstats_mfma_kernel<8, 1><<<grid, 512, 0, a.stream>>>(m);
         else rowstats_mfma_kernel<8, 2><<<grid, 512, 0, a.stream>>>(m);        // measured faster than 16 x 1 for this sweep
     }
-    const size_t n = (size_t)groups * p.RP;
-    rowstats_merge_mfma_kernel<<<(unsigned)((n + 255) / 256), 256, 0, a.stream>>>(
-        m.part, a.row_max, a.row_sum, (float2*)a.stat_p, groups, p.nsplit, p.RP, p.tauP, s.tau, m.g, s.Hq, s.Hkv,
-        a.nnz, a.nnz ? (size_t)s.B * s.L * s.Hq : 0, s.lens, s.L, s.m);
     return hipGetLastError();
 }
 
-hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool have_stat_p) {
+hipError_t launch_colsweep_mfma(const ScoreArgs& a, bool merge_partials) {
     const vlc_shape& s = a.s;
     const Plan p = make_plan(s);
     MfmaArgs m = make_args(a, p);
-    if (have_stat_p) m.stat_p = (const float2*)a.stat_p;
+    if (merge_partials) m.part_in = m.part;          // sweep 1 ran just before on the same workspace
     dim3 grid(p.nsplit, s.B * s.L * s.Hkv);
     const int total_rb = p.RP / 32;
     for (int rb0 = 0; rb0 < total_rb; rb0 += kMaxRowBlocksPerLaunch) {
