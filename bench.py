@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_FLOPS = 2.5e15
 # HBM-side bytes of one all-layer decode launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # counter reads for a plain 256 MiB copy), measured offline on the default run of a config: 10 % budget,
 # 100 decode steps.  The figures and the commands are in profiles/all_kernels_cfg*.md.
-MEASURED_DECODE_TRAFFIC_MIB = {1: 45.12 + 1.27, 2: 551.94 + 7.33}
+MEASURED_DECODE_TRAFFIC_MIB = {1: 45.12 + 1.27, 2: 551.95 + 7.33}
 
 
 def main() -> int:
