@@ -195,10 +195,27 @@ def main() -> int:
     achieved = alg_bytes / (dec_launch_us * 1e-6) / 1e9
     default_run = alpha == (1, 10) and T == 100 and cfg.cid in MEASURED_DECODE_TRAFFIC_MIB and not args.kv_fp8
     traffic = int(MEASURED_DECODE_TRAFFIC_MIB[cfg.cid] * 1048576) if default_run else None
+    # ---- what a plain copy reaches on this machine: torch's device-to-device copy of 1 GiB (HBM both ways) and of a
+    # buffer as large as one decode launch's bytes (cache-resident for the small workloads), read + write counted
+    def copy_rate(nbytes, reps=10):
+        src = torch.empty((int(nbytes),), dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        return 2.0 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    copy_big = copy_rate(1 << 30)
+    copy_same = copy_rate(max(1 << 20, int(alg_bytes) // 2))           # the copy moves twice its size
     roofline = {"bound": "hbm", "kernel": "decode_kernel (one ragged launch over all layers)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "algorithmic_bytes_per_launch": int(alg_bytes), "launch_us": round(dec_launch_us, 3)}
+                "algorithmic_bytes_per_launch": int(alg_bytes), "launch_us": round(dec_launch_us, 3),
+                "copy_kernel_GBps": {"1GiB": round(copy_big, 1), "same_bytes_as_launch": round(copy_same, 1)},
+                "frac_of_copy_kernel": round(achieved / copy_big, 4)}
 
     result = {
         "metric": METRIC, "value": round(comp_ms / cfg.B, 4), "unit": "ms/request (KV compress)",
