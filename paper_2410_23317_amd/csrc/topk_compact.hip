@@ -18,14 +18,24 @@ namespace {
 // Everything is staged in LDS so that the serial prefix sums never wait on global memory.
 constexpr int kLayoutMaxBL = 2048;     // B*L entries staged in LDS (the shape check admits no larger batch)
 
-__global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__ k, const int32_t* __restrict__ lens,
-                                                     int B, int L, int Hkv, int m, int tau,
-                                                     int d, int T_max, int64_t slots_per_request, int unit_slots,
-                                                     int64_t max_items, CacheDev dev) {
+struct LayoutArgs {
+    const int32_t* k;          // [B, L] budgets as the caller passed them
+    const int32_t* lens;       // [B, 2] per-request (m, tau), or null
+    int B, L, Hkv, m, tau, d, T_max, unit_slots;
+    int64_t slots_per_request, max_items;
+};
+
+// Runs in one block of NT threads (every thread of the block must enter).
+template <int NT>
+__device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
+    const int32_t* __restrict__ k = a.k;
+    const int32_t* __restrict__ lens = a.lens;
+    const int B = a.B, L = a.L, Hkv = a.Hkv, m = a.m, tau = a.tau, d = a.d, T_max = a.T_max, unit_slots = a.unit_slots;
+    const int64_t slots_per_request = a.slots_per_request, max_items = a.max_items;
     __shared__ int32_t sKept[kLayoutMaxBL];
     __shared__ int32_t sFirst[kLayoutMaxBL];        // first work item of (b, l), kv head 0
     __shared__ int64_t sSlot[kLayoutMaxBL];
-    __shared__ int64_t sScan[256], sScan2[256];
+    __shared__ int64_t sScan[NT], sScan2[NT];
     __shared__ int32_t sFullFirst[kLayoutMaxBL], sPartFirst[kLayoutMaxBL];
     __shared__ int sTotals[2];
     __shared__ int sBad;
@@ -35,7 +45,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
     if (tid == 0) sBad = 0;
     __syncthreads();
     // per-request lengths: checked here (the only place with an error channel), kept in the cache
-    for (int b = tid; b < B; b += blockDim.x) {
+    for (int b = tid; b < B; b += NT) {
         int mb = m, tb = tau;
         if (lens) {
             mb = lens[2 * b]; tb = lens[2 * b + 1];
@@ -44,7 +54,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         const ReqLen rl = request_len(lens, b, m, tau);
         dev.lens[2 * b] = rl.m; dev.lens[2 * b + 1] = rl.tau;
     }
-    for (int x = tid; x < BL; x += blockDim.x) {
+    for (int x = tid; x < BL; x += NT) {
         int kk = k[x];
         if (kk < 1 || kk > request_len(lens, x / L, m, tau).m) {
             set_sticky(dev.status, VLC_ERR_INVALID_ARG, x / L, x % L, kk);
@@ -52,10 +62,10 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         }
         sKept[x] = kk;
     }
-    for (int x = tid; x < BL * Hkv; x += blockDim.x) dev.counters[x] = 0;
+    for (int x = tid; x < BL * Hkv; x += NT) dev.counters[x] = 0;
     __syncthreads();
     // slab offsets, one thread per request; a request whose budgets do not fit keeps nothing
-    for (int b = tid; b < B; b += blockDim.x) {
+    for (int b = tid; b < B; b += NT) {
         int64_t acc = 0;
         for (int l = 0; l < L; ++l) acc += sKept[b * L + l] + T_max;
         const bool over = acc > slots_per_request;
@@ -73,7 +83,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
     // a run of consecutive entries, the run totals are scanned across the block, then every thread
     // walks its run again from its offset.
     {
-        const int per = (BL + 255) / 256;
+        const int per = (BL + NT - 1) / NT;
         const int y0 = tid * per, y1 = min(BL, y0 + per);
         int64_t run = 0, run2 = 0;              // run2 packs (full units << 32) | partly filled units
         for (int y = y0; y < y1; ++y) {
@@ -84,7 +94,7 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         sScan[tid] = run;
         sScan2[tid] = run2;
         __syncthreads();
-        for (int o = 1; o < 256; o <<= 1) {
+        for (int o = 1; o < NT; o <<= 1) {
             const int64_t v = tid >= o ? sScan[tid - o] : 0;
             const int64_t v2 = tid >= o ? sScan2[tid - o] : 0;
             __syncthreads();
@@ -92,14 +102,14 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
             sScan2[tid] += v2;
             __syncthreads();
         }
-        const int64_t total = sScan[255];
-        if (tid == 0) { sTotals[0] = (int)(sScan2[255] >> 32); sTotals[1] = (int)(sScan2[255] & 0xffffffff); }
+        const int64_t total = sScan[NT - 1];
+        if (tid == 0) { sTotals[0] = (int)(sScan2[NT - 1] >> 32); sTotals[1] = (int)(sScan2[NT - 1] & 0xffffffff); }
         if (total > max_items) {            // cannot happen for budgets that passed the capacity check
             if (tid == 0) {
                 set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
                 sBad = 1;
             }
-            for (int l = tid; l <= L + 1; l += 256) dev.layer_item_start[l] = 0;
+            for (int l = tid; l <= L + 1; l += NT) dev.layer_item_start[l] = 0;
         } else {
             int64_t acc = sScan[tid] - run, acc2 = sScan2[tid] - run2;
             for (int y = y0; y < y1; ++y) {
@@ -116,14 +126,14 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         }
     }
     __syncthreads();
-    for (int x = tid; x < BL; x += blockDim.x) {
+    for (int x = tid; x < BL; x += NT) {
         dev.kept[x] = sKept[x];
         dev.slot_off[x] = sSlot[x];
     }
     if (sBad) return;
     const int n_full = sTotals[0], n_part = sTotals[1];
     if (tid == 0) dev.layer_item_start[L + 1] = n_full;         // decode reverses the walk over the full units on odd steps
-    for (int x = tid; x < BL * Hkv; x += blockDim.x) {
+    for (int x = tid; x < BL * Hkv; x += NT) {
         const int h = x % Hkv, bl = x / Hkv, b = bl / L, l = bl % L;
         const int kk = sKept[bl];
         const int nu = kk ? (kk + T_max + unit_slots - 1) / unit_slots : 1;
@@ -152,6 +162,8 @@ __global__ __launch_bounds__(256) void layout_kernel(const int32_t* __restrict__
         }
     }
 }
+
+__global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a, CacheDev dev) { layout_body<256>(a, dev); }
 
 // Order-preserving map float -> uint32 (larger float, larger key).
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -197,19 +209,61 @@ __device__ __forceinline__ void for_keys(const uint32_t (&key)[NK > 0 ? NK : 1],
 // decode-query attention, the top-k set S* is found the same way with the cache's own budget and no
 // recent window, and instead of emitting it the block counts how many positions the cache already holds
 // lie in S*: hits_out[row] = |kept ∩ S*|.
-template <int NK, bool HIT>
+// FOLD = true (small batches, where a one-block kernel and its launch gap show): the grid has one block more
+// than there are rows, and block 0 does the layout kernel's work while the others select.  A selecting
+// block then cannot read the layout's results: it derives its row's budget and slab offset from the caller's
+// budgets by the layout's own rules (a budget outside [1, m_b] keeps nothing; a request whose slabs do not
+// fit keeps nothing).
+template <int NK, bool HIT, bool FOLD>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores, CacheDev dev,
                                                              int L, int Hkv, int m, int ragged, int T_max, int n_recent,
                                                              int recent_num, int recent_den,
                                                              int32_t* __restrict__ idx_out,
-                                                             int32_t* __restrict__ hits_out, float* __restrict__ rate_out) {
+                                                             int32_t* __restrict__ hits_out, float* __restrict__ rate_out,
+                                                             LayoutArgs la) {
+    static_assert(!(HIT && FOLD), "the hit count reads a cache that is already laid out");
     constexpr int kSelSub = NK == 8 ? 4 : 16;                  // short rows: few adds, the clear and the sum dominate
     __shared__ __align__(16) uint32_t hist[256 * kSelSub];
     __shared__ uint32_t sel_bin, sel_above;
     __shared__ uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
-    const int row = blockIdx.x;
+    if constexpr (FOLD) {
+        if (blockIdx.x == 0) {                       // first, so that it starts with the first rows
+            layout_body<kSelThreads>(la, dev);
+            return;
+        }
+    }
+    const int row = FOLD ? (int)blockIdx.x - 1 : (int)blockIdx.x;
     const int hkv = row % Hkv, bl = row / Hkv;
-    const int kk = dev.kept[bl];
+    int kk, mb;
+    int64_t slot_off;
+    if constexpr (FOLD) {
+        __shared__ long long sSum[2 * kSelWaves];
+        const int b = bl / L, l = bl % L;
+        mb = request_len(la.lens, b, m, la.tau).m;
+        long long tot = 0, before = 0;
+        for (int x = threadIdx.x; x < L; x += kSelThreads) {
+            int v = la.k[b * L + x];
+            if (v < 1 || v > mb) v = 0;
+            tot += v + T_max;
+            if (x < l) before += v + T_max;
+        }
+        for (int o = 32; o >= 1; o >>= 1) {
+            tot += __shfl_xor(tot, o, 64);
+            before += __shfl_xor(before, o, 64);
+        }
+        if ((threadIdx.x & 63) == 0) { sSum[2 * (threadIdx.x >> 6)] = tot; sSum[2 * (threadIdx.x >> 6) + 1] = before; }
+        __syncthreads();
+        tot = 0; before = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) { tot += sSum[2 * w]; before += sSum[2 * w + 1]; }
+        kk = la.k[bl];
+        if (kk < 1 || kk > mb || tot > la.slots_per_request) kk = 0;
+        slot_off = (int64_t)b * la.slots_per_request + before;
+    } else {
+        kk = dev.kept[bl];
+        mb = ragged ? dev.lens[2 * (bl / L)] : m;     // this request's prompt length (validated by the layout kernel)
+        slot_off = dev.slot_off[bl];
+    }
     if (kk == 0) {
         if (HIT && threadIdx.x == 0) {
             hits_out[row] = 0;
@@ -220,11 +274,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     // forced recent window: a count, or a fraction of this layer's budget (Sec. 5: 10 % of the budget)
     const int rcnt = HIT ? 0 : recent_den > 0 ? (int)((int64_t)kk * recent_num / recent_den) : min(max(n_recent, 0), kk);
     const int need = kk - rcnt;                // picked by score among positions [0, mc)
-    const int mb = ragged ? dev.lens[2 * (bl / L)] : m;     // this request's prompt length (validated by the layout kernel)
     const int mc = mb - rcnt;
     const int cap = kk + T_max;
     const float* s = scores + (size_t)row * m;
-    int32_t* out = dev.idx + dev.slot_off[bl] * Hkv + (int64_t)hkv * cap;
+    int32_t* out = dev.idx + slot_off * Hkv + (int64_t)hkv * cap;
     int32_t* out2 = idx_out ? idx_out + (size_t)row * m : nullptr;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seg = ((mc + kSelWaves - 1) / kSelWaves + 63) & ~63;
@@ -468,11 +521,18 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
                                int32_t* idx_out, hipStream_t st) {
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
-    layout_kernel<<<1, 256, 0, st>>>(k, lens, s.B, s.L, s.Hkv, s.m, s.tau, s.d, c.T_max, c.slots_per_request, c.unit_slots,
-                               c.max_items, c.dev);
+    LayoutArgs la{k, lens, s.B, s.L, s.Hkv, s.m, s.tau, s.d, c.T_max, c.unit_slots, c.slots_per_request, c.max_items};
+    // The layout rides along as one more block of the selection while all rows are resident at once; with more
+    // rows the 50 KB of LDS the layout needs would halve the selecting blocks per CU for nothing.
+    const char* fknob = getenv("VLC_SELECT_FOLD");               // tuning knob: 0 = always a kernel of its own
+    const bool fold = rows <= 512 && !(fknob && atoi(fknob) == 0);
+    if (!fold) layout_kernel<<<1, 256, 0, st>>>(la, c.dev);
     // values per lane of a wave's segment (an eighth of the row, rounded up to whole wave loads)
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_SELECT(NK) select_kernel<NK, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr)
+#define VLC_SELECT(NK) do { \
+        if (fold) select_kernel<NK, false, true><<<rows + 1, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la); \
+        else select_kernel<NK, false, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la); \
+    } while (0)
     if (per_lane <= 8) VLC_SELECT(8);
     else if (per_lane <= 24) VLC_SELECT(24);
     else if (per_lane <= 64) VLC_SELECT(64);
@@ -505,7 +565,7 @@ hipError_t launch_cache_hit_count(const vlc_cache& c, const float* scores_star, 
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_HITS(NK) select_kernel<NK, true><<<rows, kSelThreads, 0, st>>>(scores_star, c.dev, s.L, s.Hkv, s.m, c.ragged, c.T_max, 0, 0, 0, nullptr, hits_out, rate_out)
+#define VLC_HITS(NK) select_kernel<NK, true, false><<<rows, kSelThreads, 0, st>>>(scores_star, c.dev, s.L, s.Hkv, s.m, c.ragged, c.T_max, 0, 0, 0, nullptr, hits_out, rate_out, LayoutArgs{})
     if (per_lane <= 8) VLC_HITS(8);
     else if (per_lane <= 24) VLC_HITS(24);
     else if (per_lane <= 64) VLC_HITS(64);

@@ -87,6 +87,57 @@ def test_topk_ties_extremes_and_recent_window():
     assert idx[0].cpu().numpy().tolist() == list(range(7)) and idx[1].cpu().numpy().tolist() == list(range(7))
 
 
+@pytest.mark.parametrize("fold", ["0", "1"])
+def test_layout_as_its_own_kernel_or_inside_the_selection(fold):
+    """Small batches build the cache layout in one extra block of the selection kernel, large ones in a kernel of
+    its own.  Both forms, forced by the knob on the same batch (unequal budgets, one of them invalid): kept
+    positions against the oracle's TopK, gathered rows, the error report, and the decode work list via a decode
+    call whose result must not depend on the form."""
+    V = _V()
+    r = np.random.default_rng(11)
+    m, B, L, Hkv = 700, 2, 3, 2
+    scores = r.standard_normal((B, L, Hkv, m)).astype(np.float32)
+    kk = np.array([[40, 700, 1], [333, 0, 90]])
+    old = os.environ.get("VLC_SELECT_FOLD")
+    os.environ["VLC_SELECT_FOLD"] = fold
+    try:
+        cache, idx_out, K, Vv, view = _topk_case(V, scores, kk, 0, m, Hkv=Hkv, L=L, B=B)
+        with pytest.raises(V.VlcError) as e:
+            V.vlc_cache_status(cache)
+        assert e.value.status == V.VLC_ERR_INVALID_ARG and "k[1][1]" in str(e.value)
+        for b in range(B):
+            for l in range(L):
+                if kk[b, l] == 0:
+                    continue
+                kc, vc, idx = view(cache, b, l)
+                for h in range(Hkv):
+                    want = O.topk(scores[b, l, h].astype(np.float64), int(kk[b, l]), 0)
+                    assert np.array_equal(idx[h].cpu().numpy(), want), (b, l, h)
+                    assert np.array_equal(idx_out[b, l, h, : kk[b, l]].cpu().numpy(), want)
+                    assert torch.equal(kc[h], K[b, l, h][torch.from_numpy(want).cuda()])
+                    assert torch.equal(vc[h], Vv[b, l, h][torch.from_numpy(want).cuda()])
+        # one decode step over all layers: plain attention over the kept rows (fp64 on the host)
+        g = torch.Generator(device="cpu").manual_seed(3)
+        q = torch.randn((L, B, Hkv, 64), generator=g).cuda()
+        out = torch.full((L, B, Hkv, 64), 7.0, device="cuda")
+        V.vlc_decode_attn(cache, 0, L, q, None, None, None, out)
+        torch.cuda.synchronize()
+        for b in range(B):
+            for l in range(L):
+                if kk[b, l] == 0:
+                    assert torch.all(out[l, b] == 0)
+                    continue
+                kept = [O.topk(scores[b, l, h].astype(np.float64), int(kk[b, l]), 0) for h in range(Hkv)]
+                ref = O.decode_attn(q[l, b].cpu().numpy(), [K[b, l, h].cpu().numpy()[kept[h]] for h in range(Hkv)],
+                                    [Vv[b, l, h].cpu().numpy()[kept[h]] for h in range(Hkv)], 1.0 / np.sqrt(64))
+                np.testing.assert_allclose(out[l, b].cpu().numpy(), ref, rtol=2e-4, atol=2e-5)
+    finally:
+        if old is None:
+            os.environ.pop("VLC_SELECT_FOLD", None)
+        else:
+            os.environ["VLC_SELECT_FOLD"] = old
+
+
 def test_recent_fraction_extremes():
     """Fraction 0 keeps nothing unconditionally, fraction 1 keeps exactly the last k positions."""
     V = _V()
