@@ -522,18 +522,18 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
     const vlc_shape& s = c.shape;
     const int rows = s.B * s.L * s.Hkv;
     LayoutArgs la{k, lens, s.B, s.L, s.Hkv, s.m, s.tau, s.d, c.T_max, c.unit_slots, c.slots_per_request, c.max_items};
-    // The layout rides along as one more block of the selection while all rows are resident at once; with more
-    // rows the 50 KB of LDS the layout needs would halve the selecting blocks per CU for nothing.
-    const char* fknob = getenv("VLC_SELECT_FOLD");               // tuning knob: 0 = always a kernel of its own
-    const bool fold = rows <= 512 && !(fknob && atoi(fknob) == 0);
-    if (!fold) layout_kernel<<<1, 256, 0, st>>>(la, c.dev);
     // values per lane of a wave's segment (an eighth of the row, rounded up to whole wave loads)
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
-#define VLC_SELECT(NK) do { \
-        if (fold) select_kernel<NK, false, true><<<rows + 1, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la); \
-        else select_kernel<NK, false, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la); \
-    } while (0)
-    if (per_lane <= 8) VLC_SELECT(8);
+    // The layout rides along as one more block of the selection while all rows are resident at once and short
+    // (m <= 4096), which is where a one-block kernel and its launch gap show.  With more rows the 56 KB of LDS the
+    // layout needs would halve the selecting blocks per CU, and with longer rows, whose keys fill the register
+    // file, the extra code costs registers (spills at 64 keys per lane: 100 us instead of 40 on a 32K-token row).
+    const char* fknob = getenv("VLC_SELECT_FOLD");               // tuning knob: 0 = always a kernel of its own
+    const bool fold = rows <= 512 && per_lane <= 8 && !(fknob && atoi(fknob) == 0);
+    if (!fold) layout_kernel<<<1, 256, 0, st>>>(la, c.dev);
+#define VLC_SELECT(NK) select_kernel<NK, false, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la)
+    if (fold) select_kernel<8, false, true><<<rows + 1, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la);
+    else if (per_lane <= 8) VLC_SELECT(8);
     else if (per_lane <= 24) VLC_SELECT(24);
     else if (per_lane <= 64) VLC_SELECT(64);
     else VLC_SELECT(0);
