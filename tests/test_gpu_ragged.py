@@ -29,6 +29,16 @@ def _requests(dtype, d, Hq, Hkv, L, lens, cid0):
     ("f32", 64, 4, 2, 2, [(300, 20), (123, 9), (511, 31)]),                    # plain-ALU sweeps
 ])
 def test_ragged_batch_matches_the_oracle_request_by_request(dtype, d, Hq, Hkv, L, lens):
+    _ragged_case(dtype, d, Hq, Hkv, L, lens)
+
+
+def test_ragged_batch_with_the_layout_in_a_kernel_of_its_own(monkeypatch):
+    """The same comparison with the cache layout forced out of the selection kernel (the form large batches take)."""
+    monkeypatch.setenv("VLC_SELECT_FOLD", "0")
+    _ragged_case("bf16", 128, 8, 2, 3, [(900, 40), (333, 7), (1200, 64), (64, 64)])
+
+
+def _ragged_case(dtype, d, Hq, Hkv, L, lens):
     import paper_2410_23317_amd as V
     from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
     cfgs = _requests(dtype, d, Hq, Hkv, L, lens, cid0=300)
