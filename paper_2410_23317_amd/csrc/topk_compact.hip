@@ -239,6 +239,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     if constexpr (FOLD) {
         __shared__ long long sSum[2 * kSelWaves];
         const int b = bl / L, l = bl % L;
+        kk = la.k[bl];                                 // requested with the loads of the sum, not after its barrier
         mb = request_len(la.lens, b, m, la.tau).m;
         long long tot = 0, before = 0;
         for (int x = threadIdx.x; x < L; x += kSelThreads) {
@@ -256,7 +257,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
         tot = 0; before = 0;
 #pragma unroll
         for (int w = 0; w < kSelWaves; ++w) { tot += sSum[2 * w]; before += sSum[2 * w + 1]; }
-        kk = la.k[bl];
         if (kk < 1 || kk > mb || tot > la.slots_per_request) kk = 0;
         slot_off = (int64_t)b * la.slots_per_request + before;
     } else {
