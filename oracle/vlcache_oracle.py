@@ -9,10 +9,8 @@ code with the HIP path and must never be imported by the product package.
 
 Shapes are per (request, layer): q_win [Hq, tau, d] are the queries of the last tau
 prompt tokens (the post-vision window), k, v [Hkv, m, d] the prompt's keys/values.
-Query head h reads KV head h // g, g = Hq / Hkv.  All arithmetic is fp64 on the
-values handed in; the one exception is the ThresholdFilter decision, which is
-taken on logits rounded to fp32 (the GPU kernels' logit precision) so that both
-sides decide in the same precision.
+Query head h reads KV head h // g, g = Hq / Hkv.  All arithmetic, the ThresholdFilter
+decision of Eq. 1 included, is fp64 on the values handed in.
 
 Pins (see tests/test_oracle_pins.py): softmax rows sum to 1; sum_j psi_j = tau;
 equal logits give harmonic-number scores; one dominant key per row gives nnz = tau;
@@ -132,23 +130,21 @@ def sparsity(q_win, k, scale, p: float = 0.01, want_margin: bool = False):
     """nnz[h] = number of entries of the causal region that ThresholdFilter keeps, i.e.
     A'_{ij} >= p max_j A'_{ij}; gamma[h] = 1 - nnz[h] / region_size.
 
-    Since A'_{ij} / max_j A'_{ij} = exp(s_ij - M_i), the test is s_ij - M_i >= ln p.  It
-    is evaluated in fp32 on fp32-rounded logits (the kernels' precision).  With
-    want_margin the fp64 distance |s_ij - M_i - ln p| of every valid entry is returned
-    too (masked entries get +inf) so a harness can list borderline decisions."""
+    Since A'_{ij} / max_j A'_{ij} = exp(s_ij - M_i), the test is s_ij - M_i >= ln p (Eq. 1 is a
+    statement in real arithmetic: it is decided on the fp64 logits).  With want_margin the
+    distance |s_ij - M_i - ln p| of every valid entry is returned too (masked entries get +inf)
+    so a harness can list the decisions that a lower-precision evaluation may take the other way."""
     s = logits(q_win, k, scale)
     tau, m = s.shape[1], s.shape[2]
     valid = causal_valid(m, tau)[None]
-    s32 = s.astype(np.float32)
-    M32 = np.where(valid, s32, -np.inf).max(axis=2).astype(np.float32)
-    lnp = np.float32(math.log(p))
-    keep = valid & ((s32 - M32[:, :, None]) >= lnp)
+    M = np.where(valid, s, -np.inf).max(axis=2)
+    gap = s - M[:, :, None] - math.log(p)
+    keep = valid & (gap >= 0.0)
     nnz = keep.sum(axis=(1, 2)).astype(np.int64)
     gamma = 1.0 - nnz / float(region_size(m, tau))
     if not want_margin:
         return nnz, gamma
-    M = np.where(valid, s, -np.inf).max(axis=2)
-    margin = np.where(valid, np.abs(s - M[:, :, None] - math.log(p)), np.inf)
+    margin = np.where(valid, np.abs(gap), np.inf)
     return nnz, gamma, margin, keep
 
 

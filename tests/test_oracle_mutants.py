@@ -72,14 +72,12 @@ def _sparsity_strict(q_win, k, scale, p=0.01, want_margin=False):
     s = O.logits(q_win, k, scale)
     tau, m = s.shape[1], s.shape[2]
     valid = O.causal_valid(m, tau)[None]
-    s32 = s.astype(np.float32)
-    M32 = np.where(valid, s32, -np.inf).max(axis=2).astype(np.float32)
-    keep = valid & ((s32 - M32[:, :, None]) > np.float32(math.log(p)))
+    M = np.where(valid, s, -np.inf).max(axis=2)
+    keep = valid & ((s - M[:, :, None]) > math.log(p))
     nnz = keep.sum(axis=(1, 2)).astype(np.int64)
     gamma = 1.0 - nnz / float(O.region_size(m, tau))
     if not want_margin:
         return nnz, gamma
-    M = np.where(valid, s, -np.inf).max(axis=2)
     return nnz, gamma, np.where(valid, np.abs(s - M[:, :, None] - math.log(p)), np.inf), keep
 
 

@@ -115,11 +115,17 @@ def test_two_level_logits_count():
 
 
 def test_threshold_boundary_is_inclusive():
-    lnp = np.float32(math.log(0.01))
-    below = np.nextafter(lnp, np.float32(-np.inf))
-    k = np.array([0.0, lnp, below], dtype=np.float32).reshape(1, 3, 1)
-    q = np.ones((1, 1, 1), dtype=np.float32)
-    nnz, _ = O.sparsity(q, k, 1.0, 0.01)
+    # logits 0, ln p and the next double below ln p: s - M = ln p exactly for the second key (kept),
+    # one ulp less for the third (filtered); one ulp above is kept as well
+    lnp = math.log(0.01)
+    below, above = np.nextafter(lnp, -np.inf), np.nextafter(lnp, np.inf)
+    q = np.ones((1, 1, 1))
+    nnz, _ = O.sparsity(q, np.array([0.0, lnp, below]).reshape(1, 3, 1), 1.0, 0.01)
+    assert int(nnz[0]) == 2
+    nnz, _ = O.sparsity(q, np.array([0.0, above, below, below]).reshape(1, 4, 1), 1.0, 0.01)
+    assert int(nnz[0]) == 2
+    # the decision is taken in double precision: a gap of 1e-12 (far below fp32 resolution) decides
+    nnz, _ = O.sparsity(q, np.array([0.0, lnp - 1e-12, lnp + 1e-12]).reshape(1, 3, 1), 1.0, 0.01)
     assert int(nnz[0]) == 2
 
 
