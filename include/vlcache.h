@@ -105,6 +105,22 @@ vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k,
                      void* workspace, size_t workspace_bytes, vlc_stream stream);
 
 /*
+ * vlc_score_static -- vlc_score for callers that cannot allocate device memory or hold a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same
+ * arguments, outputs and errors as vlc_score, without the workspace: the partial row statistics live
+ * in an array built into the library, vlc_score_static_max_workspace() bytes (16 MiB) per GPU, which
+ * the GPU holds until the process ends.  A shape whose partial statistics need more is rejected with
+ * VLC_ERR_CAPACITY (use vlc_score).  The call allocates and frees nothing.  All calls on one GPU share
+ * that array: calls that may overlap on the device (different streams) race; calls ordered on one
+ * stream are fine, and nothing an earlier call left in the array is read.
+ */
+size_t     vlc_score_static_max_workspace(void);
+vlc_status vlc_score_static(const vlc_shape* shape, const void* q_win, const void* k,
+                            const float* sm_scale, float p,
+                            float* scores, float* row_max, float* row_sum, uint64_t* nnz,
+                            vlc_stream stream);
+
+/*
  * vlc_sparsity -- ThresholdFilter sparsity of the post-vision attention (paper Eq. 1, Eq. 2,
  * Alg. 1 ComputeSparsity):  gamma = 1 - nnz / D,  D = tau (m - tau) + tau (tau + 1) / 2.
  *

@@ -52,6 +52,10 @@ def _load() -> C.CDLL:
     lib.vlc_workspace_bytes.argtypes = [shp]
     lib.vlc_score.restype = C.c_int
     lib.vlc_score.argtypes = [shp, vp, vp, vp, f32, vp, vp, vp, vp, vp, sz, vp]
+    lib.vlc_score_static_max_workspace.restype = sz
+    lib.vlc_score_static_max_workspace.argtypes = []
+    lib.vlc_score_static.restype = C.c_int
+    lib.vlc_score_static.argtypes = [shp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
     lib.vlc_sparsity.restype = C.c_int
     lib.vlc_sparsity.argtypes = [shp, vp, vp, vp, vp, f32, vp, vp, vp, sz, vp]
     lib.vlc_window_attn_workspace_bytes.restype = sz
@@ -136,6 +140,15 @@ def vlc_score(shape, q_win, k, sm_scale, p, scores, row_max, row_sum, nnz, works
     _check(lib.vlc_score(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(sm_scale), float(p), _ptr(scores),
                          _ptr(row_max), _ptr(row_sum), _ptr(nnz), _ptr(workspace),
                          0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def vlc_score_static_max_workspace() -> int:
+    return lib.vlc_score_static_max_workspace()
+
+
+def vlc_score_static(shape, q_win, k, sm_scale, p, scores, row_max, row_sum, nnz) -> None:
+    _check(lib.vlc_score_static(C.byref(shape), _ptr(q_win), _ptr(k), _ptr(sm_scale), float(p), _ptr(scores),
+                                _ptr(row_max), _ptr(row_sum), _ptr(nnz), _stream()))
 
 
 def vlc_sparsity(shape, q_win, k, sm_scale, row_max, p, nnz, gamma, workspace) -> None:

@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "internal.h"
@@ -76,6 +77,33 @@ vlc::ScoreArgs score_args(const vlc_shape* s, const void* q_win, const void* k, 
     return a;
 }
 
+// ---- scratch of vlc_score_static: one array per GPU, held until the process ends ----------------
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each GPU, resolved on first use
+
+// The address of this GPU's copy of `scratch` (the array's name is a host-side handle, not a device
+// address: only the pointer resolved here may reach a kernel).
+vlc_status static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(VLC_ERR_INVALID_ARG, "device ordinal %d is outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!p) return fail(VLC_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VLC_OK;
+}
+
 hipError_t run_rowstats(const vlc::ScoreArgs& a, bool mfma) {
     return mfma ? vlc::launch_rowstats_mfma(a) : vlc::launch_rowstats_simple(a);
 }
@@ -110,6 +138,30 @@ vlc_status vlc_score(const vlc_shape* shape, const void* q_win, const void* k, c
     if (e != hipSuccess) return hip_fail(e, "vlc_score row statistics");
     e = run_colsweep(a, mfma, true);              // the counters were zeroed by the row-statistics sweep
     if (e != hipSuccess) return hip_fail(e, "vlc_score column sweep");
+    return VLC_OK;
+}
+
+size_t vlc_score_static_max_workspace(void) { return kStaticScratchBytes; }
+
+vlc_status vlc_score_static(const vlc_shape* shape, const void* q_win, const void* k, const float* sm_scale, float p,
+                            float* scores, float* row_max, float* row_sum, uint64_t* nnz, vlc_stream stream) {
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!q_win || !k || !scores || !row_max || !row_sum)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_score_static: q_win, k, scores, row_max and row_sum must not be NULL");
+    if (nnz && !(p > 0.f && p < 1.f)) return fail(VLC_ERR_INVALID_ARG, "vlc_score_static: p = %g is outside (0, 1)", p);
+    const WsPlan wp = ws_plan(*shape);
+    if (wp.part > kStaticScratchBytes)          // only the partial row statistics: the tail of a caller's workspace serves vlc_sparsity
+        return fail(VLC_ERR_CAPACITY, "vlc_score_static: this shape needs %zu bytes of partial row statistics, the built-in scratch holds %zu; "
+                                      "use vlc_score with a workspace", wp.part, kStaticScratchBytes);
+    void* ws = nullptr;
+    if (vlc_status st = static_scratch(&ws)) return st;
+    // Every partial the column sweep reads is written by the row-statistics sweep of the same call, so
+    // what an earlier call left in the array is never seen and nothing has to be cleared.
+    vlc::ScoreArgs a = score_args(shape, q_win, k, sm_scale, p, scores, row_max, row_sum, nnz, ws, stream);
+    hipError_t e = run_rowstats(a, wp.mfma);
+    if (e != hipSuccess) return hip_fail(e, "vlc_score_static row statistics");
+    e = run_colsweep(a, wp.mfma, true);
+    if (e != hipSuccess) return hip_fail(e, "vlc_score_static column sweep");
     return VLC_OK;
 }
 
