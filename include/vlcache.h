@@ -22,11 +22,15 @@
  *     small for the budgets) set a sticky flag inside the cache; the offending rows are skipped
  *     without touching memory, and vlc_cache_status reports the flag.
  *   - Query head h reads key/value head h / g (consecutive query heads share a KV head).
- *   - A vlc_cache owns device scratch (partial results, counters) and host-side append counts:
+ *   - A vlc_cache owns device scratch (partial results, counters, the per-layer append counts):
  *     calls on one cache come from one thread at a time, on one stream or on streams the caller
  *     orders; calls that overlap on the device race.  Different caches are independent.  The
  *     scoring calls keep their intermediates in the caller's workspace: calls that may overlap on
  *     the device need workspaces of their own.
+ *   - No call reads the process environment; behaviour depends on the arguments only.
+ *   - Every call may be recorded into a HIP graph (stream capture) and replayed: the kernels take
+ *     everything that changes from step to step (budgets, cache layout, append counts) from device
+ *     memory, never from values fixed at enqueue time.
  */
 #ifndef VLCACHE_H
 #define VLCACHE_H
@@ -72,7 +76,14 @@ typedef struct {
     int32_t B, L, Hq, Hkv, d, m, tau;
     int32_t dtype;             /* vlc_dtype */
     const int32_t* lens;       /* device, [B][2], or NULL */
+    int32_t flags;             /* 0, or VLC_SHAPE_* bits */
+    int32_t reserved;          /* 0 */
 } vlc_shape;
+
+/* vlc_shape.flags: take the plain-ALU scoring sweeps even where the matrix-core sweeps cover the shape
+ * (bf16, d = 128).  Same results to the scoring tolerance; a cross-check for tests.  vlc_workspace_bytes
+ * and the scoring calls read the flag from the same shape, so the size query and the call always agree. */
+#define VLC_SHAPE_SCORE_PLAIN_ALU 1
 
 const char* vlc_last_error_string(void);
 const char* vlc_version(void);
@@ -152,10 +163,10 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
  * out     [B,L,Hq,tau,d]  out  bf16 (fp32 accumulation, probabilities rounded to bf16 for the product)
  * row_max, row_sum [B,L,Hq,tau] out fp32
  * workspace               scratch of at least vlc_window_attn_workspace_bytes(shape) bytes
- * Built for dtype VLC_BF16 and d = 128 (VLC_ERR_UNIMPLEMENTED otherwise; the workspace query then
- * returns 0).  With shape->lens, rows >= tau_b of request b are left untouched.
+ * Built for dtype VLC_BF16 and d = 128: both calls return VLC_ERR_UNIMPLEMENTED otherwise (the workspace
+ * query then stores 0).  With shape->lens, rows >= tau_b of request b are left untouched.
  */
-size_t vlc_window_attn_workspace_bytes(const vlc_shape* shape);
+vlc_status vlc_window_attn_workspace_bytes(const vlc_shape* shape, size_t* bytes_out);
 vlc_status vlc_window_attn(const vlc_shape* shape, const void* q_win, const void* k, const void* v,
                            const float* sm_scale, void* out, float* row_max, float* row_sum,
                            void* workspace, size_t workspace_bytes, vlc_stream stream);
@@ -212,6 +223,38 @@ vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k
 size_t     vlc_cache_bytes_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max);
 vlc_status vlc_cache_create_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
                                 void* arena, size_t arena_bytes, vlc_cache** out);
+
+/* Cache creation with explicit options: everything the two calls above decide by themselves.  A zero in a
+ * field (or options == NULL) keeps the library's choice for that field; a value outside a field's list is
+ * VLC_ERR_INVALID_ARG.  The options only move work between blocks and kernels: results are the same to the
+ * decode tolerance, and they are fixed for the cache's lifetime.
+ *   kv_fp8            1: rows stored as E4M3 codes + per-row scale (vlc_cache_create_fp8)
+ *   unit_slots        decode launches over ALL layers cut every cached row into block-units; slots of a unit
+ *                     that lies wholly inside the kept rows: 128, 256, 512 or 1024
+ *   tail_unit_slots   slots of the units that hold the end of a row and the slots reserved for appends:
+ *                     128, 256, 512 or 1024, not above unit_slots
+ *   layer_unit_slots  slots per unit for launches over a layer range (how a model calls decode): 128, 256, 512
+ *   decode_order      1: launches over all layers walk the units layer by layer; 2: by size class (whole
+ *                     units first, then row ends, then append reserve), so the blocks dispatched last are short
+ *   decode_merge      1: the unit of a row that finishes last merges the row's partial results inside the
+ *                     decode kernel; 2: a second kernel merges
+ *   decode_zigzag     1: off; 2: a wave walks its tiles backwards on odd steps; 3: also the whole units of a
+ *                     size-class walk (what the previous step read last is what the caches still hold)
+ *   gather_rows       rows of K and of V one block of the compaction moves: 16, 32, 64 or 128
+ *   select_fold       1: the cache layout always runs as a kernel of its own; 2: always inside one more block
+ *                     of the selection kernel (B * L <= 2048 in either case) */
+typedef struct {
+    int32_t kv_fp8;
+    int32_t unit_slots, tail_unit_slots, layer_unit_slots;
+    int32_t decode_order, decode_merge, decode_zigzag;
+    int32_t gather_rows, select_fold;
+    int32_t reserved[7];       /* 0 */
+} vlc_cache_options;
+size_t     vlc_cache_bytes_opt(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
+                               const vlc_cache_options* options);
+vlc_status vlc_cache_create_opt(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
+                                const vlc_cache_options* options,
+                                void* arena, size_t arena_bytes, vlc_cache** out);
 void       vlc_cache_destroy(vlc_cache* cache);      /* frees host bookkeeping only */
 
 /* Where things live inside the arena (byte offsets from its base), for tests and tools.
@@ -232,6 +275,8 @@ typedef struct {
     int64_t slots_per_request;
     size_t scale_off;      /* FP8 caches only */
     int32_t kv_fp8;        /* 1 if the rows are FP8 E4M3 codes */
+    int32_t unit_slots, tail_unit_slots, layer_unit_slots;   /* the block-unit sizes in effect (see vlc_cache_options) */
+    size_t appended_off;   /* int32[L]: appends each layer has received since the last compaction */
 } vlc_cache_layout;
 vlc_status vlc_cache_get_layout(const vlc_cache* cache, vlc_cache_layout* out);
 
@@ -294,6 +339,14 @@ vlc_status vlc_cache_hit_rate(vlc_cache* cache, const float* scores_star, int32_
  * out          [layers in range, B, Hq, d]   out, storage dtype
  * All layers of one call must have received the same number of appends so far
  * (VLC_ERR_INVALID_ARG otherwise); appending beyond T_max is VLC_ERR_CAPACITY.
+ *
+ * The number of appends a layer has received lives in the cache's device memory: the kernel reads it,
+ * appends at slot k[b][l] + count and the launch leaves count + 1 behind.  A HIP graph that holds ONE
+ * decode step (one call over all layers, or one call per layer) can therefore be replayed once per
+ * generated token, with the new q / k_new / v_new written into the same buffers before each replay.
+ * The host keeps a count of its own for the two errors above; it advances once per call, not per replay,
+ * so replays are checked on the device only: a step beyond T_max attends without appending and sets the
+ * cache's sticky status to VLC_ERR_CAPACITY (vlc_cache_status).  vlc_topk_compact resets both counts.
  */
 vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_end,
                            const void* q, const void* k_new, const void* v_new,

@@ -29,14 +29,22 @@ class VlcError(RuntimeError):
 
 
 class vlc_shape(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("B", "L", "Hq", "Hkv", "d", "m", "tau", "dtype")] + [("lens", C.c_void_p)]
+    _fields_ = ([(n, C.c_int32) for n in ("B", "L", "Hq", "Hkv", "d", "m", "tau", "dtype")] + [("lens", C.c_void_p)] +
+                [("flags", C.c_int32), ("reserved", C.c_int32)])
 
 
 class vlc_cache_layout(C.Structure):
     _fields_ = [("status_off", C.c_size_t), ("slot_off_off", C.c_size_t), ("kept_off", C.c_size_t),
                 ("kv_off", C.c_size_t), ("idx_off", C.c_size_t), ("scratch_off", C.c_size_t),
                 ("total_bytes", C.c_size_t), ("slots_per_request", C.c_int64), ("scale_off", C.c_size_t),
-                ("kv_fp8", C.c_int32)]
+                ("kv_fp8", C.c_int32), ("unit_slots", C.c_int32), ("tail_unit_slots", C.c_int32),
+                ("layer_unit_slots", C.c_int32), ("appended_off", C.c_size_t)]
+
+
+class vlc_cache_options(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kv_fp8", "unit_slots", "tail_unit_slots", "layer_unit_slots", "decode_order",
+                                         "decode_merge", "decode_zigzag", "gather_rows", "select_fold")] + \
+               [("reserved", C.c_int32 * 7)]
 
 
 def _load() -> C.CDLL:
@@ -58,8 +66,8 @@ def _load() -> C.CDLL:
     lib.vlc_score_static.argtypes = [shp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
     lib.vlc_sparsity.restype = C.c_int
     lib.vlc_sparsity.argtypes = [shp, vp, vp, vp, vp, f32, vp, vp, vp, sz, vp]
-    lib.vlc_window_attn_workspace_bytes.restype = sz
-    lib.vlc_window_attn_workspace_bytes.argtypes = [shp]
+    lib.vlc_window_attn_workspace_bytes.restype = C.c_int
+    lib.vlc_window_attn_workspace_bytes.argtypes = [shp, C.POINTER(sz)]
     lib.vlc_window_attn.restype = C.c_int
     lib.vlc_window_attn.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.vlc_score_from_stats.restype = C.c_int
@@ -74,6 +82,10 @@ def _load() -> C.CDLL:
     lib.vlc_cache_bytes_fp8.argtypes = [shp, i32, i64]
     lib.vlc_cache_create_fp8.restype = C.c_int
     lib.vlc_cache_create_fp8.argtypes = [shp, i32, i64, vp, sz, C.POINTER(vp)]
+    lib.vlc_cache_bytes_opt.restype = sz
+    lib.vlc_cache_bytes_opt.argtypes = [shp, i32, i64, C.POINTER(vlc_cache_options)]
+    lib.vlc_cache_create_opt.restype = C.c_int
+    lib.vlc_cache_create_opt.argtypes = [shp, i32, i64, C.POINTER(vlc_cache_options), vp, sz, C.POINTER(vp)]
     lib.vlc_cache_destroy.restype = None
     lib.vlc_cache_destroy.argtypes = [vp]
     lib.vlc_cache_get_layout.restype = C.c_int
@@ -113,12 +125,15 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def make_shape(B, L, Hq, Hkv, d, m, tau, dtype, lens=None) -> vlc_shape:
+VLC_SHAPE_SCORE_PLAIN_ALU = 1
+
+
+def make_shape(B, L, Hq, Hkv, d, m, tau, dtype, lens=None, flags=0) -> vlc_shape:
     """lens: optional int32 device tensor [B, 2] of per-request (m_b, tau_b); the caller keeps it alive."""
     code = {torch.float32: VLC_F32, torch.bfloat16: VLC_BF16, "f32": VLC_F32, "bf16": VLC_BF16}.get(dtype, dtype)
     if lens is not None:
         assert lens.dtype == torch.int32 and lens.is_cuda and lens.is_contiguous() and tuple(lens.shape) == (B, 2)
-    return vlc_shape(B, L, Hq, Hkv, d, m, tau, code, None if lens is None else lens.data_ptr())
+    return vlc_shape(B, L, Hq, Hkv, d, m, tau, code, None if lens is None else lens.data_ptr(), int(flags), 0)
 
 
 def vlc_version() -> str:
@@ -158,10 +173,9 @@ def vlc_sparsity(shape, q_win, k, sm_scale, row_max, p, nnz, gamma, workspace) -
 
 
 def vlc_window_attn_workspace_bytes(shape: vlc_shape) -> int:
-    n = lib.vlc_window_attn_workspace_bytes(C.byref(shape))
-    if n == 0:
-        raise VlcError(VLC_ERR_UNIMPLEMENTED, vlc_last_error_string())
-    return n
+    n = C.c_size_t(0)
+    _check(lib.vlc_window_attn_workspace_bytes(C.byref(shape), C.byref(n)))
+    return n.value
 
 
 def vlc_window_attn(shape, q_win, k, v, sm_scale, out, row_max, row_sum, workspace) -> None:
@@ -194,16 +208,39 @@ def vlc_cache_bytes_fp8(shape, T_max, sum_k_max) -> int:
     return n
 
 
+def make_options(**kw) -> vlc_cache_options:
+    """vlc_cache_options with the named fields set and everything else 0 (the library's choice)."""
+    o = vlc_cache_options()
+    for name, value in kw.items():
+        if name == "reserved" or name not in {f[0] for f in vlc_cache_options._fields_}:
+            raise ValueError(f"vlc_cache_options has no field {name}")
+        setattr(o, name, int(value))
+    return o
+
+
+def vlc_cache_bytes_opt(shape, T_max, sum_k_max, options) -> int:
+    n = lib.vlc_cache_bytes_opt(C.byref(shape), int(T_max), int(sum_k_max), None if options is None else C.byref(options))
+    if n == 0:
+        raise VlcError(VLC_ERR_INVALID_ARG, vlc_last_error_string())
+    return n
+
+
 class Cache:
     """Owns the arena tensor and the library's host-side handle."""
 
-    def __init__(self, shape: vlc_shape, T_max: int, sum_k_max: int, device="cuda", fp8: bool = False):
-        self.shape, self.T_max, self.sum_k_max, self.fp8 = shape, int(T_max), int(sum_k_max), bool(fp8)
-        nbytes = (vlc_cache_bytes_fp8 if fp8 else vlc_cache_bytes)(shape, T_max, sum_k_max)
+    def __init__(self, shape: vlc_shape, T_max: int, sum_k_max: int, device="cuda", fp8: bool = False,
+                 options: Optional[vlc_cache_options] = None):
+        if options is None:
+            options = make_options(kv_fp8=int(bool(fp8)))
+        elif fp8:
+            options.kv_fp8 = 1
+        self.shape, self.T_max, self.sum_k_max, self.fp8 = shape, int(T_max), int(sum_k_max), bool(options.kv_fp8)
+        self.options = options
+        nbytes = vlc_cache_bytes_opt(shape, T_max, sum_k_max, options)
         self.arena = torch.empty(nbytes, dtype=torch.uint8, device=device)
         handle = C.c_void_p()
-        create = lib.vlc_cache_create_fp8 if fp8 else lib.vlc_cache_create
-        _check(create(C.byref(shape), self.T_max, self.sum_k_max, self.arena.data_ptr(), nbytes, C.byref(handle)))
+        _check(lib.vlc_cache_create_opt(C.byref(shape), self.T_max, self.sum_k_max, C.byref(options), self.arena.data_ptr(),
+                                        nbytes, C.byref(handle)))
         self.handle = handle
         lay = vlc_cache_layout()
         _check(lib.vlc_cache_get_layout(self.handle, C.byref(lay)))
@@ -227,6 +264,10 @@ def vlc_cache_create(shape, T_max, sum_k_max, device="cuda") -> Cache:
 
 def vlc_cache_create_fp8(shape, T_max, sum_k_max, device="cuda") -> Cache:
     return Cache(shape, T_max, sum_k_max, device, fp8=True)
+
+
+def vlc_cache_create_opt(shape, T_max, sum_k_max, options, device="cuda") -> Cache:
+    return Cache(shape, T_max, sum_k_max, device, options=options)
 
 
 def vlc_cache_status(cache: Cache) -> None:

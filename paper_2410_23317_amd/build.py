@@ -35,14 +35,22 @@ def _run(cmd):
     return out
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, incremental: bool = False) -> str:
+    """Compiles every source (incremental=True, a developer convenience: only those older than their object
+    file or than any header) and links the shared library."""
     os.makedirs(BUILD, exist_ok=True)
     hipcc = _hipcc()
     srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")] + \
+              [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))] + [os.path.abspath(__file__)]
+    newest_header = max(os.path.getmtime(h) for h in headers)
 
     def compile_one(src):
         obj = os.path.join(BUILD, src.replace(".hip", ".o"))
-        out = _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        path = os.path.join(CSRC, src)
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(path), newest_header):
+            return obj, ""
+        out = _run([hipcc, *FLAGS, "-c", path, "-o", obj])
         return obj, out
 
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
@@ -55,4 +63,4 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, incremental="-i" in sys.argv))

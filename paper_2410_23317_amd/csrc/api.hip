@@ -6,6 +6,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <initializer_list>
 #include <mutex>
 #include <new>
 
@@ -47,6 +48,8 @@ vlc_status check_shape(const vlc_shape* s) {
     if ((double)s->B * s->L * s->Hq * ((s->m + 255) / 256) > 2.0e9) return fail(VLC_ERR_SHAPE, "B * L * Hq * m exceeds the grid of the scoring sweeps");
     if ((int64_t)s->B * s->L > 2048) return fail(VLC_ERR_SHAPE, "B * L = %lld exceeds 2048", (long long)s->B * s->L);
     if ((double)s->m * s->d * s->Hkv * s->L * s->B > 4.0e12) return fail(VLC_ERR_SHAPE, "K tensor larger than 4e12 elements");
+    if ((s->flags & ~VLC_SHAPE_SCORE_PLAIN_ALU) != 0 || s->reserved != 0)
+        return fail(VLC_ERR_INVALID_ARG, "shape flags %#x / reserved %d: unknown bits", s->flags, s->reserved);
     return VLC_OK;
 }
 
@@ -60,8 +63,7 @@ struct WsPlan { size_t part, stats, total; bool mfma; };
 
 WsPlan ws_plan(const vlc_shape& s) {
     WsPlan w;
-    const char* force = getenv("VLC_SCORE_PATH");             // tuning knob: "simple" forces the plain-ALU sweeps
-    w.mfma = vlc::score_mfma_supported(s) && !(force && strcmp(force, "simple") == 0);
+    w.mfma = vlc::score_mfma_supported(s) && !(s.flags & VLC_SHAPE_SCORE_PLAIN_ALU);
     const size_t a = vlc::score_simple_workspace_bytes(s), b = vlc::score_mfma_workspace_bytes(s);
     w.part = align_up(a > b ? a : b, 256);
     w.stats = align_up((size_t)s.B * s.L * s.Hq * s.tau * sizeof(float), 256);
@@ -203,13 +205,14 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
     return VLC_OK;
 }
 
-size_t vlc_window_attn_workspace_bytes(const vlc_shape* shape) {
-    if (check_shape(shape) != VLC_OK) return 0;
-    if (!vlc::window_attn_supported(*shape)) {
-        fail(VLC_ERR_UNIMPLEMENTED, "vlc_window_attn: built for bf16 storage and d = 128 only");
-        return 0;
-    }
-    return vlc::window_attn_workspace_bytes(*shape);
+vlc_status vlc_window_attn_workspace_bytes(const vlc_shape* shape, size_t* bytes_out) {
+    if (!bytes_out) return fail(VLC_ERR_INVALID_ARG, "vlc_window_attn_workspace_bytes: bytes_out is NULL");
+    *bytes_out = 0;
+    if (vlc_status st = check_shape(shape)) return st;
+    if (!vlc::window_attn_supported(*shape))
+        return fail(VLC_ERR_UNIMPLEMENTED, "vlc_window_attn: built for bf16 storage and d = 128 only");
+    *bytes_out = vlc::window_attn_workspace_bytes(*shape);
+    return VLC_OK;
 }
 
 vlc_status vlc_window_attn(const vlc_shape* shape, const void* q_win, const void* k, const void* v,
@@ -269,66 +272,132 @@ vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alp
 
 struct ArenaPlan {
     vlc_cache_layout lay;
-    size_t items_off, items2_off, layer_start_off, row_first_off, partials_off, counters_off, lens_off;
-    int32_t unit_slots;
-    int64_t max_items;
+    vlc_cache_options opt;      // resolved
+    size_t items_off[2], layer_start_off[2], row_first_off[2], partials_off, counters_off, readers_off, lens_off;
+    int64_t cap[2];
 };
 
-static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, bool fp8, ArenaPlan* plan) {
+static bool one_of(int v, std::initializer_list<int> ok) {
+    for (int x : ok) if (v == x) return true;
+    return false;
+}
+
+// Upper bound on the units of a list that cuts rows into u_big units followed by u_small units (internal.h):
+// a row of k kept slots has floor(k / u_big) + ceil((k mod u_big + T_max) / u_small) units, a rejected row one.
+static int64_t list_capacity(const vlc_shape* s, int32_t T_max, int64_t spr, int ub, int us) {
+    const int64_t BL = (int64_t)s->B * s->L;
+    const int64_t by_small = (int64_t)s->B * spr / us + BL;
+    const int64_t by_big = (int64_t)s->B * spr / ub + BL * (((int64_t)ub + T_max + us - 1) / us + 1);
+    return (int64_t)s->Hkv * (by_small < by_big ? by_small : by_big);
+}
+
+static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_max, const vlc_cache_options* in, ArenaPlan* plan) {
     if (vlc_status st = check_shape(s)) return st;
+    vlc_cache_options o;
+    memset(&o, 0, sizeof(o));
+    if (in) o = *in;
+    const bool fp8 = o.kv_fp8 != 0;
+    if (!one_of(o.kv_fp8, {0, 1})) return fail(VLC_ERR_INVALID_ARG, "options: kv_fp8 = %d", o.kv_fp8);
     if (fp8 && s->dtype != VLC_BF16) return fail(VLC_ERR_DTYPE, "an FP8 cache needs bf16 storage of Q, K and V");
     if (T_max < 0 || T_max > (1 << 24)) return fail(VLC_ERR_INVALID_ARG, "T_max = %d is out of range", T_max);
     if (sum_k_max < s->L || sum_k_max > (int64_t)s->L * s->m)
         return fail(VLC_ERR_INVALID_ARG, "sum_k_max = %lld is outside [L, L*m]", (long long)sum_k_max);
+    if (!one_of(o.unit_slots, {0, 128, 256, 512, 1024}) || !one_of(o.tail_unit_slots, {0, 128, 256, 512, 1024}) ||
+        !one_of(o.layer_unit_slots, {0, 128, 256, 512}))
+        return fail(VLC_ERR_INVALID_ARG, "options: unit sizes %d / %d / %d are not among 128, 256, 512 (1024)", o.unit_slots,
+                    o.tail_unit_slots, o.layer_unit_slots);
+    if (!one_of(o.decode_order, {0, 1, 2}) || !one_of(o.decode_merge, {0, 1, 2}) || !one_of(o.decode_zigzag, {0, 1, 2, 3}) ||
+        !one_of(o.gather_rows, {0, 16, 32, 64, 128}) || !one_of(o.select_fold, {0, 1, 2}))
+        return fail(VLC_ERR_INVALID_ARG, "options: decode_order %d, decode_merge %d, decode_zigzag %d, gather_rows %d or select_fold %d "
+                                         "is not a listed value", o.decode_order, o.decode_merge, o.decode_zigzag, o.gather_rows, o.select_fold);
     vlc_cache_layout* lay = &plan->lay;
     const size_t es = fp8 ? 1 : elem_size(s->dtype);          // bytes per cached K/V element
     const size_t BL = (size_t)s->B * s->L;
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
-    // decode block-unit: 256 slots, 512 once the mean row is long (measured on the ragged budgets of
-    // the 7B shapes: per-unit overhead against balance)
-    plan->unit_slots = (sum_k_max / s->L + T_max / 2 >= 768) ? 512 : 256;
-    if (const char* e = getenv("VLC_UNIT_SLOTS")) {           // tuning knob
-        const int v = atoi(e);
-        if (v == 128 || v == 256 || v == 512) plan->unit_slots = v;
+    const int64_t mean_row = sum_k_max / s->L + T_max / 2;    // slots of an average row half-way through decode
+    // ---- the library's own choices (measured on the ragged budgets of the 7B and 34B shapes)
+    // launches over all layers: 256-slot units, 512 once the mean row is long (per-unit overhead against balance)
+    if (!o.unit_slots) {
+        o.unit_slots = mean_row >= 768 ? 512 : 256;
+        if (o.tail_unit_slots > o.unit_slots) o.unit_slots = o.tail_unit_slots;
     }
-    plan->max_items = (int64_t)s->Hkv * ((int64_t)s->B * spr / plan->unit_slots + (int64_t)BL);
-    if (plan->max_items > (int64_t)1 << 30)
-        return fail(VLC_ERR_SHAPE, "cache of %lld decode units: budgets plus reserved appends are too large", (long long)plan->max_items);
+    if (!o.tail_unit_slots) o.tail_unit_slots = o.unit_slots;
+    if (o.tail_unit_slots > o.unit_slots)
+        return fail(VLC_ERR_INVALID_ARG, "options: tail_unit_slots = %d exceeds unit_slots = %d", o.tail_unit_slots, o.unit_slots);
+    // launches over a layer range: units fine enough that one layer of the batch fills the chip
+    if (!o.layer_unit_slots) {
+        const int64_t layer_slots = (int64_t)s->B * s->Hkv * mean_row;
+        o.layer_unit_slots = layer_slots / 128 <= 2048 ? 128 : (layer_slots / 256 <= 2048 ? 256 : 512);
+    }
+    plan->cap[0] = list_capacity(s, T_max, spr, o.layer_unit_slots, o.layer_unit_slots);
+    plan->cap[1] = list_capacity(s, T_max, spr, o.unit_slots, o.tail_unit_slots);
+    // a launch over all layers whose units are all resident at once (768 blocks fit the chip) gains nothing from the
+    // size-class order, which only moves the units of a row apart
+    if (!o.decode_order) o.decode_order = plan->cap[1] > 1536 ? 2 : 1;
+    if (!o.decode_merge) o.decode_merge = 1;
+    if (!o.decode_zigzag) o.decode_zigzag = 3;
+    if (!o.gather_rows) o.gather_rows = 64;
+    if (o.gather_rows > o.layer_unit_slots) o.gather_rows = o.layer_unit_slots;
+    {
+        // The layout rides along as one more block of the selection while all rows are resident at once and short
+        // (m <= 4096), which is where a one-block kernel and its launch gap show.  With more rows the LDS the
+        // layout needs would halve the selecting blocks per CU, and with longer rows, whose keys fill the register
+        // file, the extra code costs registers (spills at 64 keys per lane).
+        const bool short_rows = s->m <= 4096;
+        if (!o.select_fold) o.select_fold = (BL * s->Hkv <= 512 && short_rows) ? 2 : 1;
+        if (o.select_fold == 2 && !short_rows) o.select_fold = 1;
+    }
+    for (int i = 0; i < 2; ++i)
+        if (plan->cap[i] > (int64_t)1 << 30)
+            return fail(VLC_ERR_SHAPE, "cache of %lld decode units: budgets plus reserved appends are too large", (long long)plan->cap[i]);
+    plan->opt = o;
     const int g = s->Hq / s->Hkv;
+    const int64_t cap_max = plan->cap[0] > plan->cap[1] ? plan->cap[0] : plan->cap[1];
     size_t off = 0;
     lay->status_off = off;      off = align_up(off + 4 * sizeof(int32_t), 256);
     lay->slot_off_off = off;    off = align_up(off + BL * sizeof(int64_t), 256);
     lay->kept_off = off;        off = align_up(off + BL * sizeof(int32_t), 256);
+    lay->appended_off = off;    off = align_up(off + (size_t)s->L * sizeof(int32_t), 256);
     lay->kv_off = off;          off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * s->d * es, 256);
     lay->idx_off = off;         off = align_up(off + (size_t)s->B * spr * s->Hkv * sizeof(int32_t), 256);
     lay->scratch_off = off;
-    plan->items_off = off;        off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
-    plan->items2_off = off;       off = align_up(off + (size_t)plan->max_items * sizeof(vlc::WorkItem), 256);
-    plan->layer_start_off = off;  off = align_up(off + (size_t)(s->L + 2) * sizeof(int32_t), 256);
-    plan->row_first_off = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
-    plan->partials_off = off;     off = align_up(off + (size_t)plan->max_items * g * (s->d + 2) * sizeof(float), 256);
+    for (int i = 0; i < 2; ++i) {
+        plan->items_off[i] = off;        off = align_up(off + (size_t)plan->cap[i] * sizeof(vlc::WorkItem), 256);
+        plan->layer_start_off[i] = off;  off = align_up(off + (size_t)(s->L + 2) * sizeof(int32_t), 256);
+        plan->row_first_off[i] = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
+    }
+    plan->partials_off = off;     off = align_up(off + (size_t)cap_max * g * (s->d + 2) * sizeof(float), 256);
     plan->counters_off = off;     off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
+    plan->readers_off = off;      off = align_up(off + (size_t)(s->L + 1) * sizeof(int32_t), 256);
     plan->lens_off = off;         off = align_up(off + (size_t)s->B * 2 * sizeof(int32_t), 256);
     lay->scale_off = off;
     if (fp8) off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * sizeof(float), 256);
     lay->kv_fp8 = fp8 ? 1 : 0;
+    lay->unit_slots = o.unit_slots; lay->tail_unit_slots = o.tail_unit_slots; lay->layer_unit_slots = o.layer_unit_slots;
     lay->total_bytes = off;
     lay->slots_per_request = spr;
     return VLC_OK;
 }
 
-static size_t cache_bytes_common(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, bool fp8) {
+static vlc_cache_options options_fp8(bool fp8) {
+    vlc_cache_options o;
+    memset(&o, 0, sizeof(o));
+    o.kv_fp8 = fp8 ? 1 : 0;
+    return o;
+}
+
+static size_t cache_bytes_common(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, const vlc_cache_options* opt) {
     ArenaPlan plan;
-    if (cache_layout(shape, T_max, sum_k_max, fp8, &plan) != VLC_OK) return 0;
+    if (cache_layout(shape, T_max, sum_k_max, opt, &plan) != VLC_OK) return 0;
     return plan.lay.total_bytes;
 }
 
-static vlc_status cache_create_common(const char* who, const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, bool fp8,
-                                      void* arena, size_t arena_bytes, vlc_cache** out) {
+static vlc_status cache_create_common(const char* who, const vlc_shape* shape, int32_t T_max, int64_t sum_k_max,
+                                      const vlc_cache_options* opt, void* arena, size_t arena_bytes, vlc_cache** out) {
     if (!out) return fail(VLC_ERR_INVALID_ARG, "%s: out is NULL", who);
     *out = nullptr;
     ArenaPlan plan;
-    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, fp8, &plan)) return st;
+    if (vlc_status st = cache_layout(shape, T_max, sum_k_max, opt, &plan)) return st;
     const vlc_cache_layout& lay = plan.lay;
     if (!arena) return fail(VLC_ERR_INVALID_ARG, "%s: arena is NULL", who);
     if (((uintptr_t)arena & 255) != 0) return fail(VLC_ERR_INVALID_ARG, "%s: arena must be 256-byte aligned", who);
@@ -343,22 +412,29 @@ static vlc_status cache_create_common(const char* who, const vlc_shape* shape, i
     c->slots_per_request = lay.slots_per_request;
     c->arena = (char*)arena;
     c->layout = lay;
-    c->unit_slots = plan.unit_slots;
-    c->max_items = plan.max_items;
+    c->opt = plan.opt;
     c->dev.status = (int32_t*)(c->arena + lay.status_off);
     c->dev.slot_off = (int64_t*)(c->arena + lay.slot_off_off);
     c->dev.kept = (int32_t*)(c->arena + lay.kept_off);
+    c->dev.appended = (int32_t*)(c->arena + lay.appended_off);
     c->dev.kv = c->arena + lay.kv_off;
     c->dev.idx = (int32_t*)(c->arena + lay.idx_off);
-    c->dev.items = (vlc::WorkItem*)(c->arena + plan.items_off);
-    c->dev.items_by_size = (vlc::WorkItem*)(c->arena + plan.items2_off);
-    c->dev.layer_item_start = (int32_t*)(c->arena + plan.layer_start_off);
-    c->dev.row_item_first = (int32_t*)(c->arena + plan.row_first_off);
+    for (int i = 0; i < 2; ++i) {
+        vlc::WorkList& wl = c->dev.list[i];
+        wl.items = (vlc::WorkItem*)(c->arena + plan.items_off[i]);
+        wl.layer_start = (int32_t*)(c->arena + plan.layer_start_off[i]);
+        wl.row_first = (int32_t*)(c->arena + plan.row_first_off[i]);
+        wl.u_big = i == 0 ? plan.opt.layer_unit_slots : plan.opt.unit_slots;
+        wl.u_small = i == 0 ? plan.opt.layer_unit_slots : plan.opt.tail_unit_slots;
+        wl.by_size = i == 1 && plan.opt.decode_order == 2;
+        wl.cap = (int32_t)plan.cap[i];
+    }
     c->dev.partials = (float*)(c->arena + plan.partials_off);
     c->dev.counters = (int32_t*)(c->arena + plan.counters_off);
+    c->dev.readers = (int32_t*)(c->arena + plan.readers_off);
     c->dev.lens = (int32_t*)(c->arena + plan.lens_off);
     c->dev.scales = (float*)(c->arena + lay.scale_off);
-    c->kv_fp8 = fp8;
+    c->kv_fp8 = plan.opt.kv_fp8 != 0;
     c->ragged = false;
     c->compacted = false;
     *out = c;
@@ -366,18 +442,27 @@ static vlc_status cache_create_common(const char* who, const vlc_shape* shape, i
 }
 
 size_t vlc_cache_bytes(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
-    return cache_bytes_common(shape, T_max, sum_k_max, false);
+    return cache_bytes_common(shape, T_max, sum_k_max, nullptr);
 }
 size_t vlc_cache_bytes_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max) {
-    return cache_bytes_common(shape, T_max, sum_k_max, true);
+    const vlc_cache_options o = options_fp8(true);
+    return cache_bytes_common(shape, T_max, sum_k_max, &o);
+}
+size_t vlc_cache_bytes_opt(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, const vlc_cache_options* options) {
+    return cache_bytes_common(shape, T_max, sum_k_max, options);
 }
 vlc_status vlc_cache_create(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
                             size_t arena_bytes, vlc_cache** out) {
-    return cache_create_common("vlc_cache_create", shape, T_max, sum_k_max, false, arena, arena_bytes, out);
+    return cache_create_common("vlc_cache_create", shape, T_max, sum_k_max, nullptr, arena, arena_bytes, out);
 }
 vlc_status vlc_cache_create_fp8(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, void* arena,
                                 size_t arena_bytes, vlc_cache** out) {
-    return cache_create_common("vlc_cache_create_fp8", shape, T_max, sum_k_max, true, arena, arena_bytes, out);
+    const vlc_cache_options o = options_fp8(true);
+    return cache_create_common("vlc_cache_create_fp8", shape, T_max, sum_k_max, &o, arena, arena_bytes, out);
+}
+vlc_status vlc_cache_create_opt(const vlc_shape* shape, int32_t T_max, int64_t sum_k_max, const vlc_cache_options* options,
+                                void* arena, size_t arena_bytes, vlc_cache** out) {
+    return cache_create_common("vlc_cache_create_opt", shape, T_max, sum_k_max, options, arena, arena_bytes, out);
 }
 
 void vlc_cache_destroy(vlc_cache* cache) { delete cache; }
@@ -398,6 +483,9 @@ vlc_status vlc_cache_status(vlc_cache* cache, vlc_stream stream) {
     if (st[0] == VLC_ERR_INVALID_ARG && st[2] == -2)
         return fail(VLC_ERR_INVALID_ARG, "request %d: per-request lengths (m_b = %d) are outside 1 <= tau_b <= min(tau, m_b), m_b <= m", st[1], st[3]);
     if (st[0] == VLC_ERR_INVALID_ARG) return fail(VLC_ERR_INVALID_ARG, "budget k[%d][%d] = %d is outside [1, m]", st[1], st[2], st[3]);
+    if (st[0] == VLC_ERR_CAPACITY && st[1] == -3)
+        return fail(VLC_ERR_CAPACITY, "decode step on layer %d after %d appends: only %d were reserved; the step attended without appending",
+                    st[2], st[3], cache->T_max);
     if (st[0] == VLC_ERR_CAPACITY) return fail(VLC_ERR_CAPACITY, "request %d: budgets plus reserved appends need %d slots, arena has %lld",
                                                st[1], st[3], (long long)cache->slots_per_request);
     return (vlc_status)st[0];
@@ -465,7 +553,7 @@ vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_
     vlc::DecodeArgs a;
     a.c = cache; a.layer_begin = layer_begin; a.n_layers = layer_end - layer_begin;
     a.q = q; a.k_new = k_new; a.v_new = v_new; a.sm_scale = sm_scale; a.out = out;
-    a.appended = appended; a.stream = (hipStream_t)stream;
+    a.stream = (hipStream_t)stream;
     hipError_t e = vlc::launch_decode(a);
     if (e != hipSuccess) return hip_fail(e, "vlc_decode_attn");
     if (k_new)

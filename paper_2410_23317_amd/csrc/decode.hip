@@ -2,10 +2,11 @@
 // phase: the new key/value is appended, then softmax(q K^T / sqrt d) V over every cached slot).
 //
 // Bandwidth-bound: every K and V row is read once and serves all g query heads of its KV group.
-// Rows are ragged (layer budgets differ by 25x), so the work is cut into block-units of BK slots
-// listed in a device-side work list that vlc_topk_compact builds; a call launches one block per
-// unit of the slice of the list that belongs to its layer range.  Inside a block-unit each of
-// the 4 waves owns NT tiles of 32 slots:
+// Rows are ragged (layer budgets differ by 25x), so the work is cut into block-units of 128 to 1024
+// slots listed in device-side work lists that vlc_topk_compact builds; a call launches one block per
+// unit of the slice of a list that belongs to its layer range (launches over a layer range are capped
+// at one resident round of blocks, which then walk the slice with the grid as stride).  Inside a
+// block-unit the tiles of 32 slots are dealt round-robin to the 4 waves:
 //   1. K and V rows are loaded 16 bytes per lane (LPR lanes per row, fully coalesced), all
 //      issued before any arithmetic;
 //   2. logits: packed-bf16 dot products (v_dot2_f32_bf16) against the g query rows held in
@@ -21,6 +22,12 @@
 // are coherent across the XCDs' L2 caches by themselves, so no cache-wide release/acquire
 // fence is needed (those cost tens of microseconds here).  Matrix cores are not used: with
 // g <= 8 query rows per KV head the work is a stream, not a contraction.
+//
+// Nothing that changes from step to step is a launch parameter: the number of appends a layer has
+// received is read from the cache (dev.appended), and the launch that appends leaves count + 1 behind.
+// Every block takes a ticket (dev.readers) right after it has read the count; the block that holds the
+// last ticket of the launch knows that every other block has read the count and writes the new one.
+// A HIP graph that holds one decode step can therefore be replayed step after step.
 #include <stdlib.h>
 
 #include <type_traits>
@@ -38,14 +45,13 @@ struct DecodeParams {
     void* out;
     const float* sm_scale;
     CacheDev dev;
-    const WorkItem* items;   // the work list this launch walks
+    WorkList wl;             // the work list this launch walks
+    int ub_shift, us_shift;  // log2 of the list's unit sizes
     int B, L, Hq, Hkv, m;
     int layer_begin, n_layers, T_max;
-    int appended;            // appends before this call
+    int append_mode;         // 0: attend only; 1: k_new / v_new are appended by this kernel; 2: they were stored by the append kernel of this call
     int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
-    int prefetch;            // next tile's loads issued early (more registers, 2 blocks per CU)
-    int zigzag;              // 1: tile order within a unit alternates between steps; 2: also the walk over the full units
-    int rev_full;            // size-class order only: walk the full units backwards in this launch
+    int zigzag;              // 1 off; 2: tile order within a unit alternates between steps; 3: also the walk over the whole units
     int kv_fp8;              // the cache rows are E4M3 codes with per-row scales
     float default_scale;
 };
@@ -73,6 +79,12 @@ __device__ __forceinline__ void store_agent(float* p, float v) {
 }
 __device__ __forceinline__ float load_agent(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(int32_t* p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int32_t add_agent(int32_t* p, int32_t v) {
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Merge the nu partials (unnormalised output, running max, running sum) of one row; partials
@@ -182,8 +194,8 @@ template <> struct IsBf16<bf16_t> { static constexpr bool value = true; };
 // expanded to bf16 (exactly) where they are consumed, the K scale multiplies the finished logit, the
 // V scale the probability before it is rounded to bf16.  Appends to such a cache are done by
 // append_fp8_kernel before this kernel runs.
-template <typename T, int D, int G, int NT, bool PF, bool Q8>
-__global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void decode_kernel(DecodeParams P) {
+template <typename T, int D, int G, bool Q8>
+__global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodeParams P) {
     constexpr bool BF = IsBf16<T>::value;
     static_assert(!Q8 || BF, "FP8 caches hold bf16 models");
     constexpr int EP = Elem<T>::kPer16B;        // elements in a 16-byte chunk
@@ -195,7 +207,6 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
     constexpr int HR = (GP + 3) / 4;            // heads per 16-lane row in the softmax step
     constexpr int KK = TK / 16;                 // slots per lane in the softmax step
     constexpr int DP = D + 2;
-    constexpr int BK = 4 * NT * TK;             // slots per block-unit
     constexpr bool SCATTER = (LPR == 16 && G <= 4);
     static_assert(G <= LPR, "one lane per head needed when parking logits");
     static_assert(NIT % 2 == 0, "P.V pairs consecutive loads");
@@ -208,37 +219,70 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int sub = lane / LPR, c = lane % LPR;
     const int srow = lane >> 4, scol = lane & 15;
-    const bool appending = P.k_new != nullptr;
-    // One block-unit per block; the hardware dispatcher balances the ragged units.  The grid is a
-    // host-side upper bound on the units of the layer range, surplus blocks leave below.  A range
-    // that starts at layer 0 starts at unit 0, so the unit record does not wait for the range lookup
-    // (the grid never exceeds the list's capacity, so a surplus block reads an unused record).
-    int w = blockIdx.x;
-    if (P.rev_full) {                           // size-class order, odd step: the full units are walked backwards, so that
-        const int nf = min(P.dev.layer_item_start[P.L + 1], (int)gridDim.x);   // what the memory-side cache kept of the last step comes first
-        const int nf8 = nf & ~7;                // whole groups of 8 change places, so a unit stays on its XCD (and its L2)
-        if (w < nf8) w = nf8 - 8 - (w & ~7) + (w & 7);
+    const WorkList wl = P.wl;
+    // ---- what the whole launch shares: the slice of the list, and the append count of its layers
+    const int begin = P.layer_begin ? wl.layer_start[P.layer_begin] : 0;
+    const int end = wl.layer_start[P.layer_begin + P.n_layers];
+    const int appended = P.dev.appended[P.layer_begin];
+    int mode = P.append_mode;
+    if (mode && appended >= P.T_max) {          // more steps than slots were reserved (only a replayed graph gets here):
+        if (blockIdx.x == 0 && tid == 0) set_sticky(P.dev.status, VLC_ERR_CAPACITY, -3, P.layer_begin, appended);
+        mode = 0;                               // attend over what the cache holds, append nothing, count nothing
     }
-    if (P.layer_begin != 0) {
-        w += P.dev.layer_item_start[P.layer_begin];
-        if (w >= P.dev.layer_item_start[P.layer_begin + P.n_layers]) return;
-    }
-    {
-        const WorkItem itv = P.items[w];
-        if (P.layer_begin == 0 && w >= P.dev.layer_item_start[P.n_layers]) return;
+    const bool appending = mode == 1;
+    const int step = appended + (mode ? 1 : 0); // appends the cache holds once this launch is done
+    // A block takes its ticket only after it has read the append count: the operand of the ticket's atomic add
+    // is produced by a statement that consumes the count.
+    int one = 1;
+    asm volatile("" : "+s"(one) : "s"(appended));
+    // The block that holds the last ticket of its layer, and then of the launch, publishes the new count.
+    auto finish = [&](int ticket, int il) {
+        const int n_layer = wl.layer_start[il + 1] - wl.layer_start[il];
+        if (ticket != n_layer - 1) return;
+        store_agent(P.dev.readers + il, 0);
+        if (P.n_layers > 1) {
+            if (add_agent(P.dev.readers + P.L, 1) != P.n_layers - 1) return;
+            store_agent(P.dev.readers + P.L, 0);
+        }
+        for (int l = P.layer_begin; l < P.layer_begin + P.n_layers; ++l) store_agent(P.dev.appended + l, step);
+    };
+    // One block-unit per block while the grid covers the slice (the hardware dispatcher then balances the ragged
+    // units); a capped grid walks the rest of the slice with the grid as stride.  The grid is a host-side upper
+    // bound on the units of the layer range, surplus blocks leave below.
+#pragma unroll 1
+    for (int w0 = blockIdx.x;; w0 += gridDim.x) {
+        int w = w0;
+        if (wl.by_size && P.zigzag > 2 && (step & 1)) {   // size-class order, odd step: the whole units are walked backwards, so that
+            const int nf = min(wl.layer_start[P.L + 1], (int)gridDim.x);   // what the memory-side cache kept of the last step comes first
+            const int nf8 = nf & ~7;            // whole groups of 8 change places, so a unit stays on its XCD (and its L2)
+            if (w < nf8) w = nf8 - 8 - (w & ~7) + (w & 7);
+        }
+        w += begin;
+        if (w >= wl.cap) break;
+        const WorkItem itv = wl.items[w];       // requested together with the bounds of the slice
+        if (w >= end) break;
+        if (w0 != (int)blockIdx.x) __syncthreads();       // the previous unit's merge buffers are free again
         const int kept = uniform(itv.kept), key0 = uniform(itv.key0), row_abs = uniform(itv.row_abs);
         const int unit = uniform(itv.unit), ib = uniform(itv.b), il = uniform(itv.l), canon = uniform(itv.canon);
+        const int ucap = uniform(itv.ucap);
         const int64_t kbase = uniform64(itv.kbase), idx_base = uniform64(itv.idx_base);
         const int lr = il - P.layer_begin;
-        const int hkv = row_abs % P.Hkv;
+        const int hkv = row_abs - (ib * P.L + il) * P.Hkv;
+        int ticket = -1;
+        if (mode && tid == 0) ticket = add_agent(P.dev.readers + il, one);
         T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + ib) * P.Hq + (size_t)hkv * G) * D;
         if (kept == 0) {                        // request rejected at compaction: defined output, no reads
             for (int x = tid; x < G * D; x += 256) Elem<T>::store(outp + x, 0.f);
-            return;
+            if (mode && tid == 0) finish(ticket, il);
+            continue;
         }
-        const int len = kept + P.appended + (appending ? 1 : 0);
-        if (key0 >= len) return;                // unit reserved for later appends
-        const int nu = (len + BK - 1) / BK;     // units of this row that hold slots now
+        const int len = kept + step;
+        if (key0 >= len) {                      // unit reserved for later appends
+            if (mode && tid == 0) finish(ticket, il);
+            continue;
+        }
+        const int nbig = kept >> P.ub_shift;    // units of this row that hold slots now: the whole ones, and the small ones up to len
+        const int nu = nbig + ((len - (nbig << P.ub_shift) + (1 << P.us_shift) - 1) >> P.us_shift);
         const int cap = kept + P.T_max;
         const int new_slot = appending ? len - 1 : -1;
         const T* Kbase = reinterpret_cast<const T*>(P.dev.kv) + kbase;
@@ -266,9 +310,8 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
 #pragma unroll
             for (int e = 0; e < EP; ++e) acc[h][e] = 0.f;
 
-        // K and V of a tile sit in separate register buffers.  The K loads of the next tile are issued
-        // as soon as the logits have consumed the current ones, the V loads as soon as P.V is done, so
-        // a wave keeps 8 to 16 KB in flight while it computes.
+        // K and V of a tile sit in separate register buffers; all 16 KB of a tile are requested before any
+        // arithmetic on it.
         uint4 kb[Q8 ? 1 : NIT], vb[Q8 ? 1 : NIT];
         uint2 kb8[Q8 ? NIT : 1], vb8[Q8 ? NIT : 1];
         float ksc[Q8 ? NIT : 1], vsc[Q8 ? KK : 1];
@@ -317,7 +360,7 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                     vb[i] = full ? load_row(std::true_type{}, Vbase, vnew, t0, i) : load_row(std::false_type{}, Vbase, vnew, t0, i);
             }
         };
-        auto tile_body = [&](auto fullc, int t0, bool more) {
+        auto tile_body = [&](auto fullc, int t0) {
             constexpr bool FULL = decltype(fullc)::value;
             // ---- logits of 32 slots -> LDS
 #pragma unroll
@@ -348,7 +391,6 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                     if (c < G) sL[wave][i * KPI + sub][c] = live ? mine * rs : -INFINITY;
                 }
             }
-            if (more) issue_k(t0 + 4 * TK);
             __builtin_amdgcn_wave_barrier();
             // ---- softmax bookkeeping: 16-lane row r handles heads r*HR.., lane column j slots j, j+16
             float corr_row[HR];
@@ -433,32 +475,30 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
                     }
                 }
             }
-            if (more) issue_v(t0 + 4 * TK);
             __builtin_amdgcn_wave_barrier();
         };
         // tiles of the unit are dealt round-robin to the 4 waves, so a partly filled unit keeps all of them busy.
         // A wave walks its tiles forwards on even steps and backwards on odd ones: a cache that is a little
         // larger than an L2 then finds the tiles it touched last in the previous step first in this one.
         const int tw0 = key0 + wave * TK;
-        const int nt_w = tw0 < len ? min(NT, (len - tw0 + 4 * TK - 1) / (4 * TK)) : 0;     // tiles of this wave that hold slots
-        const bool rev = !PF && P.zigzag && ((P.appended + (appending ? 1 : 0)) & 1);
+        const int nt_w = tw0 < len ? min(ucap / (4 * TK), (len - tw0 + 4 * TK - 1) / (4 * TK)) : 0;     // tiles of this wave that hold slots
+        const bool rev = P.zigzag > 1 && (step & 1);
         if (nt_w > 0) { const int t0 = tw0 + (rev ? nt_w - 1 : 0) * 4 * TK; issue_k(t0); issue_v(t0); }
 #pragma unroll 1
         for (int i = 0; i < nt_w; ++i) {
             const int t0 = tw0 + (rev ? nt_w - 1 - i : i) * 4 * TK;
-            const bool more = PF && (i + 1 < nt_w);
-            if (!PF && i > 0) { issue_k(t0); issue_v(t0); }
+            if (i > 0) { issue_k(t0); issue_v(t0); }
             const bool full = (t0 + TK <= len);
-            if (full) tile_body(std::true_type{}, t0, more); else tile_body(std::false_type{}, t0, more);
+            if (full) tile_body(std::true_type{}, t0); else tile_body(std::false_type{}, t0);
         }
 
         // The unit that holds the new slot also stores the new row into the cache.
-        if (!Q8 && appending && new_slot >= key0 && new_slot < key0 + BK && wave == 0 && sub == 0) {
+        if (!Q8 && appending && new_slot >= key0 && new_slot < key0 + ucap && wave == 0 && sub == 0) {
             T* kdst = const_cast<T*>(Kbase) + (int64_t)new_slot * D;
             T* vdst = const_cast<T*>(Vbase) + (int64_t)new_slot * D;
             *reinterpret_cast<uint4*>(kdst + c * EP) = *reinterpret_cast<const uint4*>(knew + c * EP);
             *reinterpret_cast<uint4*>(vdst + c * EP) = *reinterpret_cast<const uint4*>(vnew + c * EP);
-            if (c == 0) P.dev.idx[idx_base + new_slot] = P.m + P.appended;
+            if (c == 0) P.dev.idx[idx_base + new_slot] = P.m + appended;
         }
 
         // ---- sum the row groups of the wave, then merge the 4 waves through LDS
@@ -509,23 +549,29 @@ __global__ __launch_bounds__(256, (G <= 4 && !(PF && NT > 1) ? 3 : 2)) void deco
             }
         }
         if (nu > 1 && P.merge_mode == 1) {
-            // The barrier waits for this block's device-scope stores to complete; the counter then
-            // publishes them.  The unit that counts nu - 1 predecessors merges.
+            // Publication of the partials.  They were written with device-scope stores, which go through to the
+            // memory side of the XCDs' L2 caches.  Every thread first waits until its own stores have been
+            // acknowledged (a workgroup barrier alone does not drain another wave's outstanding stores), then
+            // the barrier orders all four waves before thread 0, and only then does thread 0 add to the row's
+            // counter.  The unit that counts nu - 1 predecessors therefore finds every partial of the row in
+            // memory; it reads them with device-scope loads, which do not hit a stale line of its own L2.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             int32_t* counter = P.dev.counters + row_abs;
-            if (tid == 0)
-                sLast = (__hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nu - 1) ? 1 : 0;
+            if (tid == 0) sLast = (add_agent(counter, 1) == nu - 1) ? 1 : 0;
             __syncthreads();
             if (sLast) {
                 merge_partials<T, D, G, true>(P.dev.partials + (size_t)(canon - unit) * G * DP, outp, nu, tid);
-                if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0) store_agent(counter, 0);
             }
         }
+        if (mode && tid == 0) finish(ticket, il);
     }
 }
 
 // Append to an FP8 cache: one wave per (layer, request, KV head) row quantises the new key and value
 // (lanes [0, LPR) the key, [LPR, 2 LPR) the value) into slot kept + appended and records its position.
+// The attention kernel that follows in the same call counts the step (append mode 2).
 template <int D>
 __global__ __launch_bounds__(64) void append_fp8_kernel(DecodeParams P) {
     constexpr int LPR = D / 8;
@@ -535,11 +581,12 @@ __global__ __launch_bounds__(64) void append_fp8_kernel(DecodeParams P) {
     const int lr = row / (P.Hkv * P.B);
     const int bl = b * P.L + P.layer_begin + lr;
     const int kept = P.dev.kept[bl];
-    if (kept == 0) return;
+    const int appended = P.dev.appended[P.layer_begin];
+    if (kept == 0 || appended >= P.T_max) return;      // rejected row; no slot left (the attention kernel reports it)
     const int cap = kept + P.T_max;
     const int64_t so = P.dev.slot_off[bl];
     const int64_t kbase = ((so * 2 * P.Hkv) + (int64_t)hkv * cap) * D;
-    const int slot = kept + P.appended;
+    const int slot = kept + appended;
     const int lane = threadIdx.x, c = lane % LPR, which = lane / LPR;         // which: 0 key, 1 value, others idle
     const bf16_t* src = reinterpret_cast<const bf16_t*>(which == 1 ? P.v_new : P.k_new) +
                         ((size_t)(lr * P.B + b) * P.Hkv + hkv) * D + c * 8;
@@ -550,13 +597,13 @@ __global__ __launch_bounds__(64) void append_fp8_kernel(DecodeParams P) {
         *reinterpret_cast<uint2*>(P.dev.kv + kbase + voff * D + (int64_t)slot * D + c * 8) = q;
         if (c == 0) P.dev.scales[kbase / D + voff + slot] = scale;
     }
-    if (lane == 0) P.dev.idx[so * P.Hkv + (int64_t)hkv * cap + slot] = P.m + P.appended;
+    if (lane == 0) P.dev.idx[so * P.Hkv + (int64_t)hkv * cap + slot] = P.m + appended;
 }
 
-// Second kernel of merge mode 2: one block per (layer, request, KV head) row.
-template <typename T, int D, int G, int NT>
+// Second kernel of merge mode 2: one block per (layer, request, KV head) row.  It runs after the attention
+// kernel of the same call, so the append count it reads already includes this call's step.
+template <typename T, int D, int G>
 __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
-    constexpr int BK = 4 * NT * 32;
     const int row = blockIdx.x;
     const int hkv = row % P.Hkv;
     const int b = (row / P.Hkv) % P.B;
@@ -564,55 +611,48 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
     const int bl = b * P.L + P.layer_begin + lr;
     const int kept = P.dev.kept[bl];
     if (kept == 0) return;
-    const int len = kept + P.appended + (P.k_new ? 1 : 0);
-    const int nu = (len + BK - 1) / BK;
+    const int len = kept + P.dev.appended[P.layer_begin];
+    const int nbig = kept >> P.ub_shift;
+    const int nu = nbig + ((len - (nbig << P.ub_shift) + (1 << P.us_shift) - 1) >> P.us_shift);
     if (nu == 1) return;
     T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + b) * P.Hq + (size_t)hkv * G) * D;
-    const int w0 = P.dev.row_item_first[(size_t)bl * P.Hkv + hkv];
+    const int w0 = P.wl.row_first[(size_t)bl * P.Hkv + hkv];
     merge_partials<T, D, G, false>(P.dev.partials + (size_t)w0 * G * (D + 2), outp, nu, threadIdx.x);
 }
 
-template <typename T, int D, int G, int NT>
-hipError_t launch_nt(const DecodeParams& P, int grid, int rows, hipStream_t st) {
-
+template <typename T, int D, int G>
+hipError_t launch_one(const DecodeParams& P, int grid, int rows, hipStream_t st) {
+    bool done = false;
     if constexpr (IsBf16<T>::value) {
         if (P.kv_fp8) {
-            decode_kernel<T, D, G, NT, false, true><<<grid, 256, 0, st>>>(P);
-            if (P.merge_mode == 2) decode_merge_kernel<T, D, G, NT><<<rows, 256, 0, st>>>(P);
-            return hipGetLastError();
+            decode_kernel<T, D, G, true><<<grid, 256, 0, st>>>(P);
+            done = true;
         }
     }
-    if (P.prefetch && NT > 1) decode_kernel<T, D, G, NT, true, false><<<grid, 256, 0, st>>>(P);
-    else decode_kernel<T, D, G, NT, false, false><<<grid, 256, 0, st>>>(P);
-    if (P.merge_mode == 2) decode_merge_kernel<T, D, G, NT><<<rows, 256, 0, st>>>(P);
+    if (!done) decode_kernel<T, D, G, false><<<grid, 256, 0, st>>>(P);
+    if (P.merge_mode == 2) decode_merge_kernel<T, D, G><<<rows, 256, 0, st>>>(P);
     return hipGetLastError();
 }
 
-template <typename T, int D, int G>
-hipError_t launch_one(const DecodeParams& P, int nt, int grid, int rows, hipStream_t st) {
-    if (nt == 1) return launch_nt<T, D, G, 1>(P, grid, rows, st);
-    if (nt == 2) return launch_nt<T, D, G, 2>(P, grid, rows, st);
-    return launch_nt<T, D, G, 4>(P, grid, rows, st);
-}
-
 template <typename T, int D>
-hipError_t launch_g(const DecodeParams& P, int g, int nt, int grid, int rows, hipStream_t st) {
+hipError_t launch_g(const DecodeParams& P, int g, int grid, int rows, hipStream_t st) {
     switch (g) {
-        case 1: return launch_one<T, D, 1>(P, nt, grid, rows, st);
-        case 2: return launch_one<T, D, 2>(P, nt, grid, rows, st);
-        case 3: return launch_one<T, D, 3>(P, nt, grid, rows, st);
-        case 4: return launch_one<T, D, 4>(P, nt, grid, rows, st);
-        case 5: return launch_one<T, D, 5>(P, nt, grid, rows, st);
-        case 6: return launch_one<T, D, 6>(P, nt, grid, rows, st);
-        case 7: return launch_one<T, D, 7>(P, nt, grid, rows, st);
-        case 8: return launch_one<T, D, 8>(P, nt, grid, rows, st);
+        case 1: return launch_one<T, D, 1>(P, grid, rows, st);
+        case 2: return launch_one<T, D, 2>(P, grid, rows, st);
+        case 3: return launch_one<T, D, 3>(P, grid, rows, st);
+        case 4: return launch_one<T, D, 4>(P, grid, rows, st);
+        case 5: return launch_one<T, D, 5>(P, grid, rows, st);
+        case 6: return launch_one<T, D, 6>(P, grid, rows, st);
+        case 7: return launch_one<T, D, 7>(P, grid, rows, st);
+        case 8: return launch_one<T, D, 8>(P, grid, rows, st);
     }
     return hipErrorInvalidValue;
 }
 
-int env_int(const char* name, int dflt) {
-    const char* e = getenv(name);
-    return e ? atoi(e) : dflt;
+int log2i(int v) {
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
 }
 
 }  // namespace
@@ -623,40 +663,39 @@ hipError_t launch_decode(const DecodeArgs& a) {
     DecodeParams P;
     P.q = a.q; P.k_new = a.k_new; P.v_new = a.v_new; P.out = a.out; P.sm_scale = a.sm_scale;
     P.dev = c.dev;
-    // A launch over all layers of a cache with more units than fit the chip at once (768 blocks)
-    // walks the size-class order, so that the blocks dispatched last are the short units.  When all
-    // units are resident together the order only moves the units of a row apart, which measured slower.
-    const int order = env_int("VLC_DECODE_ORDER", 0);                     // tuning knob: 1 layer-major, 2 size classes
-    const bool by_size = order == 2 || (order != 1 && c.max_items > 1536);
-    P.items = (a.layer_begin == 0 && a.n_layers == s.L && by_size) ? c.dev.items_by_size : c.dev.items;
+    // A launch over all layers walks list 1 (coarser units; by size class once the cache has more units than
+    // fit the chip at once, so that the blocks dispatched last are short), a launch over a layer range list 0
+    // (fine units in layer order, so that one layer of the batch still fills the chip).
+    const bool all_layers = a.layer_begin == 0 && a.n_layers == s.L;
+    P.wl = c.dev.list[all_layers ? 1 : 0];
+    P.ub_shift = log2i(P.wl.u_big); P.us_shift = log2i(P.wl.u_small);
     P.B = s.B; P.L = s.L; P.Hq = s.Hq; P.Hkv = s.Hkv; P.m = s.m;
     P.layer_begin = a.layer_begin; P.n_layers = a.n_layers; P.T_max = c.T_max;
-    P.appended = a.appended;
+    P.append_mode = a.k_new ? 1 : 0;
     P.default_scale = 1.0f / sqrtf((float)s.d);
-    P.merge_mode = env_int("VLC_DECODE_MERGE", 1) == 2 ? 2 : 1;          // tuning knobs
-    P.prefetch = env_int("VLC_DECODE_PREFETCH", 0);
-    P.zigzag = env_int("VLC_DECODE_ZIGZAG", 2);                           // tuning knob: 0 off, 1 tiles only
-    P.rev_full = (P.items == c.dev.items_by_size && P.zigzag > 1 && ((a.appended + (a.k_new ? 1 : 0)) & 1)) ? 1 : 0;
+    P.merge_mode = c.opt.decode_merge;
+    P.zigzag = c.opt.decode_zigzag;
     P.kv_fp8 = c.kv_fp8 ? 1 : 0;
     const int rows = a.n_layers * s.B * s.Hkv;
-    // Upper bound on the block-units of the layer range: every row at the full prompt length, and
-    // never more than the whole work list.
-    const int64_t bk = c.unit_slots;
-    int64_t grid = (int64_t)rows * (((int64_t)s.m + c.T_max + bk - 1) / bk);
-    if (grid > c.max_items) grid = c.max_items;
+    // Upper bound on the block-units of the layer range: every row at the full prompt length, and never more
+    // than the whole work list.  A launch over a layer range is capped at one resident round of blocks (3 per
+    // CU); its blocks walk the slice with the grid as stride.  The budgets, and with them the true number of
+    // units, are known on the device only.
+    int64_t grid = (int64_t)rows * (((int64_t)s.m + c.T_max) / P.wl.u_small + 1);
+    if (grid > P.wl.cap) grid = P.wl.cap;
+    if (!all_layers && grid > 768) grid = 768;
     if (grid < 1) grid = 1;
     const int g = s.Hq / s.Hkv;
-    const int nt = (int)(bk / 128);
     if (c.kv_fp8 && a.k_new) {
         // the new rows are quantised into their slots first; the attention kernel then sees them as cached
         if (s.d == 64) append_fp8_kernel<64><<<rows, 64, 0, a.stream>>>(P);
         else append_fp8_kernel<128><<<rows, 64, 0, a.stream>>>(P);
         P.k_new = nullptr; P.v_new = nullptr;
-        P.appended = a.appended + 1;
+        P.append_mode = 2;
     }
     if (s.dtype == VLC_F32)
-        return s.d == 64 ? launch_g<float, 64>(P, g, nt, (int)grid, rows, a.stream) : launch_g<float, 128>(P, g, nt, (int)grid, rows, a.stream);
-    return s.d == 64 ? launch_g<bf16_t, 64>(P, g, nt, (int)grid, rows, a.stream) : launch_g<bf16_t, 128>(P, g, nt, (int)grid, rows, a.stream);
+        return s.d == 64 ? launch_g<float, 64>(P, g, (int)grid, rows, a.stream) : launch_g<float, 128>(P, g, (int)grid, rows, a.stream);
+    return s.d == 64 ? launch_g<bf16_t, 64>(P, g, (int)grid, rows, a.stream) : launch_g<bf16_t, 128>(P, g, (int)grid, rows, a.stream);
 }
 
 }  // namespace vlc

@@ -13,11 +13,14 @@ namespace vlc {
 constexpr int kMaxLayers = 1024;
 constexpr int kScoreChunk = 256;       // keys per block of the generic scoring sweeps
 
-// One block-unit of decode work: `unit_slots` consecutive cache slots of one (b, l, kv head) row.
-// Built on the device by vlc_topk_compact in two orders: by (layer, request, kv head, unit), so that
-// a layer range is a contiguous slice of the list, and by size class (full units, then the partly
-// filled last units, then units that only hold slots reserved for appends) for launches over all
-// layers, where the blocks dispatched last should be the short ones.
+// One block-unit of decode work: consecutive cache slots [key0, key0 + ucap) of one (b, l, kv head) row.
+// vlc_topk_compact builds two lists of them on the device.  A row is cut into floor(kept / u_big) units of
+// u_big slots followed by units of u_small slots that hold the end of the row and the append reserve.
+//   list 0 (launches over a layer range): ordered by (layer, request, kv head, unit), so that a layer
+//           range is a contiguous slice; also drives the gather;
+//   list 1 (launches over all layers): the same order, or by size class (all u_big units, then the small
+//           units that hold kept rows, then the units that only hold append reserve), so that the blocks
+//           dispatched last are the short ones.
 struct WorkItem {
     int32_t row_abs;                   // (b*L + l)*Hkv + hkv
     int32_t key0;                      // first slot of the unit
@@ -26,10 +29,19 @@ struct WorkItem {
     int64_t kbase;                     // element offset of the row's K slab inside the kv region
     int64_t idx_base;                  // offset of the row's kept-index list inside the idx region
     int32_t b, l;
-    int32_t canon;                     // index of this unit in the (layer, request, kv head, unit) order
-    int32_t pad;
+    int32_t canon;                     // index of this unit in the (layer, request, kv head, unit) order of its list
+    int32_t ucap;                      // slots of the unit
 };
 static_assert(sizeof(WorkItem) == 48, "WorkItem layout");
+
+struct WorkList {
+    WorkItem* items;                   // [cap]
+    int32_t* layer_start;              // [L+2]: canon index of each layer's first unit, [L] the number of units, [L+1] the number of u_big units
+    int32_t* row_first;                // [B*L*Hkv]: canon index of each row's first unit
+    int32_t u_big, u_small;            // powers of two, u_small <= u_big
+    int32_t by_size;                   // items are stored by size class (else in canon order)
+    int32_t cap;                       // capacity in units
+};
 
 struct CacheDev {                      // device pointers into the caller's arena
     int32_t* status;                   // [4]
@@ -37,12 +49,11 @@ struct CacheDev {                      // device pointers into the caller's aren
     int32_t* kept;                     // [B*L]
     char* kv;
     int32_t* idx;
-    WorkItem* items;                   // [max_items], layer-major order
-    WorkItem* items_by_size;           // [max_items], the same units by size class
-    int32_t* layer_item_start;         // [L+2]: first unit of each layer, the number of units, the number of full units
-    int32_t* row_item_first;           // [B*L*Hkv]
-    float* partials;                   // [max_items][g][d + 2]
-    int32_t* counters;                 // [B*L*Hkv]
+    WorkList list[2];
+    float* partials;                   // [max list cap][g][d + 2]
+    int32_t* counters;                 // [B*L*Hkv] units of a row that have left their partial result
+    int32_t* appended;                 // [L] appends each layer has received since the last compaction
+    int32_t* readers;                  // [L + 1] blocks of a launch that have read the append count: per layer, [L] per launch
     int32_t* lens;                     // [B][2] copy of the per-request (m_b, tau_b) of the last compaction
     float* scales;                     // FP8 caches: one fp32 scale per K row and per V row, laid out like the rows
 };
@@ -54,15 +65,14 @@ struct vlc_cache {
     int32_t T_max;
     int64_t sum_k_max;
     int64_t slots_per_request;
-    int32_t unit_slots;                // slots per decode block-unit (128, 256 or 512)
-    int64_t max_items;
+    vlc_cache_options opt;             // every field resolved (no zeros left)
     char* arena;
     vlc_cache_layout layout;
     vlc::CacheDev dev;
     bool compacted;
     bool kv_fp8;                       // rows stored as E4M3 codes + per-row scale
     bool ragged;                       // the last compaction had per-request lengths (dev.lens is valid)
-    int32_t appended[vlc::kMaxLayers]; // decode appends so far, per layer
+    int32_t appended[vlc::kMaxLayers]; // decode appends enqueued so far, per layer (the device keeps the count the kernels use)
 };
 
 namespace vlc {
@@ -132,7 +142,6 @@ struct DecodeArgs {
     const void* v_new;
     const float* sm_scale;
     void* out;
-    int appended;               // appends of these layers BEFORE this call
     hipStream_t stream;
 };
 hipError_t launch_decode(const DecodeArgs& a);

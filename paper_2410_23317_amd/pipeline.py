@@ -25,7 +25,7 @@ class VLCachePath:
     def __init__(self, shape: V.vlc_shape, alpha: Tuple[int, int] = (1, 10), p: float = 0.01,
                  T_max: int = 128, n_recent: int = 0, device: str = "cuda", want_idx: bool = False,
                  recent_frac: Optional[Tuple[int, int]] = None, lens: Optional[torch.Tensor] = None,
-                 kv_fp8: bool = False):
+                 kv_fp8: bool = False, options: Optional[V.vlc_cache_options] = None):
         s = shape
         self.lens = lens                      # the [B, 2] tensor behind shape.lens (ragged batches), kept alive here
         self.shape, self.alpha, self.p, self.T_max, self.n_recent = s, alpha, float(p), int(T_max), int(n_recent)
@@ -43,7 +43,11 @@ class VLCachePath:
         self.idx_out = torch.full((s.B, s.L, s.Hkv, s.m), -1, dtype=i32, device=dev) if want_idx else None
         b_tot = (alpha[0] * s.L * s.m) // alpha[1]
         self.sum_k_max = min(s.L * s.m, b_tot + s.L * k_min_tokens(s.m))
-        self.cache = (V.vlc_cache_create_fp8 if kv_fp8 else V.vlc_cache_create)(s, self.T_max, self.sum_k_max, device)
+        if options is not None:
+            options.kv_fp8 = int(bool(kv_fp8)) or options.kv_fp8
+            self.cache = V.vlc_cache_create_opt(s, self.T_max, self.sum_k_max, options, device)
+        else:
+            self.cache = (V.vlc_cache_create_fp8 if kv_fp8 else V.vlc_cache_create)(s, self.T_max, self.sum_k_max, device)
 
     # -- after prefill ---------------------------------------------------------------------
     def score(self, q_win, k, sm_scale) -> None:
@@ -104,7 +108,8 @@ class VLCachePath:
             if self.lens is not None:             # same prompt lengths, a one-row window for every request
                 lens1 = self.lens.clone()
                 lens1[:, 1] = 1
-            one = V.make_shape(s.B, s.L, s.Hq, s.Hkv, s.d, s.m, 1, "f32" if s.dtype == V.VLC_F32 else "bf16", lens=lens1)
+            one = V.make_shape(s.B, s.L, s.Hq, s.Hkv, s.d, s.m, 1, "f32" if s.dtype == V.VLC_F32 else "bf16", lens=lens1,
+                               flags=s.flags)
             dev = self.scores.device
             self._star = dict(
                 shape=one, lens=lens1, scores=torch.empty_like(self.scores),

@@ -14,9 +14,9 @@ def torch_dtype(cfg):
     return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
 
 
-def make_shape(cfg):
+def make_shape(cfg, flags=0):
     import paper_2410_23317_amd as V
-    return V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
+    return V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype, flags=flags)
 
 
 def upload(cfg, want_v=True, workers=16):
@@ -95,8 +95,10 @@ def out_tol(cfg):
 
 
 def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, requests_to_check=None, per_layer_decode=False,
-                  dev=None, recent_frac=None):
-    """Whole path on the GPU; oracle on every (or the listed) request/layer."""
+                  dev=None, recent_frac=None, options=None, steps_entry_point=False, T_max=None):
+    """Whole path on the GPU; oracle on every (or the listed) request/layer.  options: fields of
+    vlc_cache_options; steps_entry_point: all decode steps enqueued by one vlc_decode_attn_steps call
+    (how bench.py runs them) instead of one vlc_decode_attn call per step."""
     import paper_2410_23317_amd as V
     from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
 
@@ -105,8 +107,8 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
     shape = make_shape(cfg)
     if dev is None:
         dev = upload(cfg)
-    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=max(n_steps, 1), n_recent=n_recent, want_idx=True,
-                       recent_frac=recent_frac)
+    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=max(n_steps, 1) if T_max is None else T_max, n_recent=n_recent,
+                       want_idx=True, recent_frac=recent_frac, options=None if options is None else V.make_options(**options))
     path.compress(dev["q_win"], dev["k"], dev["v"], dev["sm_scale"])
     path.status()
     torch.cuda.synchronize()
@@ -167,15 +169,25 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
     # decode steps: the GPU appends into its cache, the oracle into its own lists
     dt = torch_dtype(cfg)
     out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device="cuda")
-    for step in range(n_steps):
-        d_dev, d_host = decode_upload(cfg, step)
-        if per_layer_decode:
-            for l in range(cfg.L):
-                path.decode(l, l + 1, d_dev["q"][l], d_dev["k_new"][l], d_dev["v_new"][l], dev["sm_scale"], out[l])
-        else:
-            path.decode(0, cfg.L, d_dev["q"], d_dev["k_new"], d_dev["v_new"], dev["sm_scale"], out)
+    if steps_entry_point and n_steps:
+        hosts = [W.decode_step_inputs(cfg, t) for t in range(n_steps)]
+        stack = {n: torch.from_numpy(np.stack([h[n] for h in hosts])).to(dt).cuda() for n in ("q", "k_new", "v_new")}
+        out_all = torch.empty((n_steps, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device="cuda")
+        path.decode_steps(0, cfg.L, n_steps, stack["q"], stack["k_new"], stack["v_new"], dev["sm_scale"], out_all)
         torch.cuda.synchronize()
-        got = out.float().cpu().numpy()
+        out_all = out_all.float().cpu().numpy()
+    for step in range(n_steps):
+        if steps_entry_point:
+            d_host, got = hosts[step], out_all[step]
+        else:
+            d_dev, d_host = decode_upload(cfg, step)
+            if per_layer_decode:
+                for l in range(cfg.L):
+                    path.decode(l, l + 1, d_dev["q"][l], d_dev["k_new"][l], d_dev["v_new"][l], dev["sm_scale"], out[l])
+            else:
+                path.decode(0, cfg.L, d_dev["q"], d_dev["k_new"], d_dev["v_new"], dev["sm_scale"], out)
+            torch.cuda.synchronize()
+            got = out.float().cpu().numpy()
         for (b, l), (kc, vc) in caches.items():
             for h in range(cfg.Hkv):
                 kc[h] = np.concatenate([kc[h], d_host["k_new"][l, b, h][None]], 0)
@@ -190,6 +202,9 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
         assert np.array_equal(gk.float().cpu().numpy()[0], kc[0])
         assert np.array_equal(gv.float().cpu().numpy()[0], vc[0])
         assert gi[0, -1].item() == cfg.m + n_steps - 1
+        lay = path.cache.layout
+        count = path.cache.arena[lay.appended_off: lay.appended_off + 4 * cfg.L].view(torch.int32)
+        assert count.tolist() == [n_steps] * cfg.L, "the device-side append counts"
     print("[decode ok]", flush=True)
     return path
 

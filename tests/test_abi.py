@@ -69,7 +69,10 @@ def test_argument_validation_happens_before_any_launch(V):
 
 def test_window_attn_and_score_from_stats_validate_before_any_launch(V):
     f32 = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
-    assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32)) == 0 and "bf16" in V.vlc_last_error_string()
+    nbytes = C.c_size_t(7)
+    assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32), C.byref(nbytes)) == V.VLC_ERR_UNIMPLEMENTED
+    assert nbytes.value == 0 and "bf16" in V.vlc_last_error_string()
+    assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32), None) == V.VLC_ERR_INVALID_ARG
     assert V.lib.vlc_window_attn(C.byref(f32), 1, 1, 1, None, 1, 1, 1, 1, 1 << 30, None) == V.VLC_ERR_UNIMPLEMENTED
     s = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16")
     sp = C.byref(s)
@@ -110,6 +113,55 @@ def test_cache_bookkeeping_errors(V):
     assert V.lib.vlc_cache_hit_rate(h, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG        # cache not filled yet
     assert V.lib.vlc_cache_hit_rate(None, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG
     V.lib.vlc_cache_destroy(h)
+
+
+def test_cache_options_are_validated_and_reported(V):
+    s = V.make_shape(4, 32, 32, 8, 128, 10368, 64, "bf16")
+    sum_k = 33177 + 32 * 104
+    lay = V.vlc_cache_layout()
+    h = C.c_void_p()
+
+    def create(**kw):
+        o = V.make_options(**kw)
+        n = V.lib.vlc_cache_bytes_opt(C.byref(s), 100, sum_k, C.byref(o))
+        if n == 0:
+            return None
+        assert V.lib.vlc_cache_create_opt(C.byref(s), 100, sum_k, C.byref(o), 4096, n, C.byref(h)) == V.VLC_OK
+        assert V.lib.vlc_cache_get_layout(h, C.byref(lay)) == V.VLC_OK and lay.total_bytes == n
+        V.lib.vlc_cache_destroy(h)
+        return (lay.unit_slots, lay.tail_unit_slots, lay.layer_unit_slots)
+
+    default = create()
+    assert default[0] in (256, 512, 1024) and default[1] <= default[0] and default[2] in (128, 256, 512)
+    assert V.vlc_cache_bytes(s, 100, sum_k) == V.vlc_cache_bytes_opt(s, 100, sum_k, None)     # NULL options = the defaults
+    assert create(unit_slots=1024, tail_unit_slots=128, layer_unit_slots=256) == (1024, 128, 256)
+    assert create(unit_slots=128) == (128, 128, default[2])
+    for bad in (dict(unit_slots=100), dict(unit_slots=128, tail_unit_slots=256), dict(layer_unit_slots=1024), dict(decode_merge=3),
+                dict(decode_order=-1), dict(decode_zigzag=4), dict(gather_rows=48), dict(select_fold=3), dict(kv_fp8=2)):
+        assert create(**bad) is None, bad
+        assert "options" in V.vlc_last_error_string()
+    # an FP8 cache needs bf16 storage
+    f32 = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
+    o = V.make_options(kv_fp8=1)
+    assert V.lib.vlc_cache_bytes_opt(C.byref(f32), 8, 120, C.byref(o)) == 0
+    assert V.lib.vlc_cache_create_opt(C.byref(f32), 8, 120, C.byref(o), 4096, 1 << 30, C.byref(h)) == V.VLC_ERR_DTYPE
+
+
+def test_shape_flags(V):
+    s = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16")
+    plain = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16", flags=V.VLC_SHAPE_SCORE_PLAIN_ALU)
+    assert V.vlc_workspace_bytes(s) > 0 and V.vlc_workspace_bytes(plain) > 0
+    bad = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16", flags=6)
+    assert V.lib.vlc_workspace_bytes(C.byref(bad)) == 0
+    assert V.lib.vlc_score(C.byref(bad), 1, 1, None, 0.01, 1, 1, 1, None, 1, 1 << 30, None) == V.VLC_ERR_INVALID_ARG
+
+
+def test_library_does_not_read_the_environment():
+    """Behaviour depends on the arguments only: no source of the library calls getenv."""
+    csrc = os.path.join(ROOT, "paper_2410_23317_amd", "csrc")
+    for f in os.listdir(csrc):
+        text = open(os.path.join(csrc, f)).read()
+        assert "getenv" not in text and "environ" not in text, f
 
 
 def test_product_package_does_not_import_the_oracle():

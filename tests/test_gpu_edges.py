@@ -48,11 +48,12 @@ def test_allocate_bit_exact_on_random_counts_including_clips():
     assert k.cpu().numpy().tolist() == [O.allocate(np.zeros((4, 2), dtype=np.int64), 1000, 1, 10)[0].tolist()]
 
 
-def _topk_case(V, scores, kk, n_recent, m, Hkv=2, L=1, B=1, T_max=2, d=64):
+def _topk_case(V, scores, kk, n_recent, m, Hkv=2, L=1, B=1, T_max=2, d=64, options=None):
     """Run vlc_topk_compact alone on given scores [B,L,Hkv,m] and budgets [B,L]; returns (path-like cache, idx_out, K, Vv)."""
     from paper_2410_23317_amd.pipeline import cache_layer_view
     shape = V.make_shape(B, L, Hkv, Hkv, d, m, 1, "f32")
-    cache = V.vlc_cache_create(shape, T_max, min(L * m, int(max(kk.sum(1).max(), L))))
+    cache = V.vlc_cache_create_opt(shape, T_max, min(L * m, int(max(kk.sum(1).max(), L))),
+                                   V.make_options(**(options or {})))
     g = torch.Generator(device="cpu").manual_seed(1)
     K = torch.randn((B, L, Hkv, m, d), generator=g).cuda()
     Vv = torch.randn((B, L, Hkv, m, d), generator=g).cuda()
@@ -87,10 +88,10 @@ def test_topk_ties_extremes_and_recent_window():
     assert idx[0].cpu().numpy().tolist() == list(range(7)) and idx[1].cpu().numpy().tolist() == list(range(7))
 
 
-@pytest.mark.parametrize("fold", ["0", "1"])
+@pytest.mark.parametrize("fold", [1, 2])
 def test_layout_as_its_own_kernel_or_inside_the_selection(fold):
     """Small batches build the cache layout in one extra block of the selection kernel, large ones in a kernel of
-    its own.  Both forms, forced by the knob on the same batch (unequal budgets, one of them invalid): kept
+    its own.  Both forms, forced by the cache option on the same batch (unequal budgets, one of them invalid): kept
     positions against the oracle's TopK, gathered rows, the error report, and the decode work list via a decode
     call whose result must not depend on the form."""
     V = _V()
@@ -98,44 +99,36 @@ def test_layout_as_its_own_kernel_or_inside_the_selection(fold):
     m, B, L, Hkv = 700, 2, 3, 2
     scores = r.standard_normal((B, L, Hkv, m)).astype(np.float32)
     kk = np.array([[40, 700, 1], [333, 0, 90]])
-    old = os.environ.get("VLC_SELECT_FOLD")
-    os.environ["VLC_SELECT_FOLD"] = fold
-    try:
-        cache, idx_out, K, Vv, view = _topk_case(V, scores, kk, 0, m, Hkv=Hkv, L=L, B=B)
-        with pytest.raises(V.VlcError) as e:
-            V.vlc_cache_status(cache)
-        assert e.value.status == V.VLC_ERR_INVALID_ARG and "k[1][1]" in str(e.value)
-        for b in range(B):
-            for l in range(L):
-                if kk[b, l] == 0:
-                    continue
-                kc, vc, idx = view(cache, b, l)
-                for h in range(Hkv):
-                    want = O.topk(scores[b, l, h].astype(np.float64), int(kk[b, l]), 0)
-                    assert np.array_equal(idx[h].cpu().numpy(), want), (b, l, h)
-                    assert np.array_equal(idx_out[b, l, h, : kk[b, l]].cpu().numpy(), want)
-                    assert torch.equal(kc[h], K[b, l, h][torch.from_numpy(want).cuda()])
-                    assert torch.equal(vc[h], Vv[b, l, h][torch.from_numpy(want).cuda()])
-        # one decode step over all layers: plain attention over the kept rows (fp64 on the host)
-        g = torch.Generator(device="cpu").manual_seed(3)
-        q = torch.randn((L, B, Hkv, 64), generator=g).cuda()
-        out = torch.full((L, B, Hkv, 64), 7.0, device="cuda")
-        V.vlc_decode_attn(cache, 0, L, q, None, None, None, out)
-        torch.cuda.synchronize()
-        for b in range(B):
-            for l in range(L):
-                if kk[b, l] == 0:
-                    assert torch.all(out[l, b] == 0)
-                    continue
-                kept = [O.topk(scores[b, l, h].astype(np.float64), int(kk[b, l]), 0) for h in range(Hkv)]
-                ref = O.decode_attn(q[l, b].cpu().numpy(), [K[b, l, h].cpu().numpy()[kept[h]] for h in range(Hkv)],
-                                    [Vv[b, l, h].cpu().numpy()[kept[h]] for h in range(Hkv)], 1.0 / np.sqrt(64))
-                np.testing.assert_allclose(out[l, b].cpu().numpy(), ref, rtol=2e-4, atol=2e-5)
-    finally:
-        if old is None:
-            os.environ.pop("VLC_SELECT_FOLD", None)
-        else:
-            os.environ["VLC_SELECT_FOLD"] = old
+    cache, idx_out, K, Vv, view = _topk_case(V, scores, kk, 0, m, Hkv=Hkv, L=L, B=B, options=dict(select_fold=fold))
+    with pytest.raises(V.VlcError) as e:
+        V.vlc_cache_status(cache)
+    assert e.value.status == V.VLC_ERR_INVALID_ARG and "k[1][1]" in str(e.value)
+    for b in range(B):
+        for l in range(L):
+            if kk[b, l] == 0:
+                continue
+            kc, vc, idx = view(cache, b, l)
+            for h in range(Hkv):
+                want = O.topk(scores[b, l, h].astype(np.float64), int(kk[b, l]), 0)
+                assert np.array_equal(idx[h].cpu().numpy(), want), (b, l, h)
+                assert np.array_equal(idx_out[b, l, h, : kk[b, l]].cpu().numpy(), want)
+                assert torch.equal(kc[h], K[b, l, h][torch.from_numpy(want).cuda()])
+                assert torch.equal(vc[h], Vv[b, l, h][torch.from_numpy(want).cuda()])
+    # one decode step over all layers: plain attention over the kept rows (fp64 on the host)
+    g = torch.Generator(device="cpu").manual_seed(3)
+    q = torch.randn((L, B, Hkv, 64), generator=g).cuda()
+    out = torch.full((L, B, Hkv, 64), 7.0, device="cuda")
+    V.vlc_decode_attn(cache, 0, L, q, None, None, None, out)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for l in range(L):
+            if kk[b, l] == 0:
+                assert torch.all(out[l, b] == 0)
+                continue
+            kept = [O.topk(scores[b, l, h].astype(np.float64), int(kk[b, l]), 0) for h in range(Hkv)]
+            ref = O.decode_attn(q[l, b].cpu().numpy(), [K[b, l, h].cpu().numpy()[kept[h]] for h in range(Hkv)],
+                                [Vv[b, l, h].cpu().numpy()[kept[h]] for h in range(Hkv)], 1.0 / np.sqrt(64))
+            np.testing.assert_allclose(out[l, b].cpu().numpy(), ref, rtol=2e-4, atol=2e-5)
 
 
 def test_recent_fraction_extremes():
@@ -266,15 +259,12 @@ def test_plain_alu_scoring_path_agrees_with_the_matrix_core_path():
     cfg = _small_cfg(cid=82, m=1500, n_visual=1400, tau=50, Hq=14, Hkv=2)        # g = 7, tau not a multiple of 32
     dev = upload(cfg, want_v=False)
     res = {}
-    for mode in ("mfma", "simple"):
-        os.environ["VLC_SCORE_PATH"] = mode
-        try:
-            path = VLCachePath(make_shape(cfg), alpha=(1, 5), T_max=1)
-            path.score(dev["q_win"], dev["k"], dev["sm_scale"])
-            torch.cuda.synchronize()
-            res[mode] = (path.scores.cpu().numpy(), path.row_max.cpu().numpy(), path.row_sum.cpu().numpy(), path.nnz.cpu().numpy())
-        finally:
-            os.environ.pop("VLC_SCORE_PATH", None)
+    for mode, flags in (("mfma", 0), ("simple", V.VLC_SHAPE_SCORE_PLAIN_ALU)):
+        path = VLCachePath(make_shape(cfg, flags=flags), alpha=(1, 5), T_max=1)
+        path.score(dev["q_win"], dev["k"], dev["sm_scale"])
+        torch.cuda.synchronize()
+        res[mode] = (path.scores.cpu().numpy(), path.row_max.cpu().numpy(), path.row_sum.cpu().numpy(), path.nnz.cpu().numpy())
+    assert not np.array_equal(res["mfma"][0], res["simple"][0]), "the flag did not change the kernels that ran"
     np.testing.assert_allclose(res["mfma"][0], res["simple"][0], rtol=5e-5, atol=1e-7)
     np.testing.assert_allclose(res["mfma"][1], res["simple"][1], rtol=2e-6, atol=2e-5)
     np.testing.assert_allclose(res["mfma"][2], res["simple"][2], rtol=5e-5)
@@ -383,27 +373,148 @@ def test_whole_path_replays_from_a_hip_graph():
         assert torch.equal(out_g, out_e), rep
 
 
-@pytest.mark.parametrize("env", [{"VLC_UNIT_SLOTS": "128"}, {"VLC_UNIT_SLOTS": "128", "VLC_DECODE_MERGE": "2"},
-                                 {"VLC_UNIT_SLOTS": "256"}, {"VLC_UNIT_SLOTS": "128", "VLC_DECODE_ORDER": "2"},
-                                 {"VLC_UNIT_SLOTS": "256", "VLC_DECODE_ORDER": "2", "VLC_DECODE_MERGE": "2"},
-                                 {"VLC_UNIT_SLOTS": "512", "VLC_DECODE_ORDER": "2"}, {"VLC_UNIT_SLOTS": "512", "VLC_DECODE_ZIGZAG": "0"},
-                                 {"VLC_UNIT_SLOTS": "256", "VLC_DECODE_ZIGZAG": "1", "VLC_DECODE_ORDER": "2"}])
-def test_decode_merges_across_units(env):
+@pytest.mark.parametrize("opt", [
+    dict(unit_slots=128), dict(unit_slots=128, decode_merge=2), dict(unit_slots=256),
+    dict(unit_slots=128, decode_order=2), dict(unit_slots=256, decode_order=2, decode_merge=2),
+    dict(unit_slots=512, decode_order=2), dict(unit_slots=512, decode_zigzag=1),
+    dict(unit_slots=256, decode_zigzag=2, decode_order=2), dict(unit_slots=512, tail_unit_slots=128, decode_order=2),
+    dict(unit_slots=1024, tail_unit_slots=256, decode_order=2, decode_merge=2), dict(unit_slots=512, tail_unit_slots=128, decode_order=1),
+], ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
+@pytest.mark.parametrize("per_layer", [False, True], ids=["all-layers", "per-layer"])
+def test_decode_merges_across_units(opt, per_layer):
     """Rows longer than one block-unit: partial results merged in-kernel (device-scope counter) or by the
-    second kernel, with the work list walked layer-major or by size class, tiles and full units walked
-    forwards and backwards on alternate steps or always forwards, all against the oracle."""
+    second kernel, with the work list walked layer-major or by size class, uniform or mixed unit sizes, tiles and
+    whole units walked forwards and backwards on alternate steps or always forwards, all against the oracle.
+    Launches per layer take the layer list, whose unit size follows the same option here."""
     from gpu_util import run_and_check
     cfg = _small_cfg(cid=85, m=1300, n_visual=1200, L=2, B=2, alphas=((1, 2),), Hq=14, Hkv=2)
-    old = {k: os.environ.get(k) for k in env}
-    os.environ.update(env)
-    try:
-        run_and_check(cfg, (1, 2), 3)
-    finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
+    opt = dict(opt, layer_unit_slots=min(512, opt.get("tail_unit_slots", opt["unit_slots"])))
+    run_and_check(cfg, (1, 2), 3, options=opt, per_layer_decode=per_layer)
+
+
+def _direct_cache(V, cfg, kk, T_max, options):
+    """A cache filled by vlc_topk_compact with GIVEN budgets kk [B, L] (scores are the workload's own); returns
+    the path-like pieces and the oracle's per-(b, l) lists of kept K and V rows."""
+    from gpu_util import make_shape, upload
+    from paper_2410_23317_amd.pipeline import VLCachePath
+    dev = upload(cfg)
+    path = VLCachePath(make_shape(cfg), alpha=(1, 2), T_max=T_max, options=V.make_options(**options))
+    path.score(dev["q_win"], dev["k"], dev["sm_scale"])
+    path.topk_compact(dev["k"], dev["v"], k=torch.from_numpy(kk.astype(np.int32)).cuda())
+    path.status()
+    scales = W.sm_scale(cfg)
+    caches = {}
+    for b in range(cfg.B):
+        for l in range(cfg.L):
+            t = W.layer_inputs(cfg, b, l)
+            psi = O.score(t["q_win"], t["k"], scales[l])[0]
+            idx = [O.topk(psi[h], int(kk[b, l])) for h in range(cfg.Hkv)]
+            caches[(b, l)] = ([t["k"][h][idx[h]] for h in range(cfg.Hkv)], [t["v"][h][idx[h]] for h in range(cfg.Hkv)])
+    return path, dev, caches, scales
+
+
+def _oracle_step(cfg, caches, scales, d_host, got, step, what):
+    from gpu_util import assert_close, out_tol
+    for (b, l), (kc, vc) in caches.items():
+        for h in range(cfg.Hkv):
+            kc[h] = np.concatenate([kc[h], d_host["k_new"][l, b, h][None]], 0)
+            vc[h] = np.concatenate([vc[h], d_host["v_new"][l, b, h][None]], 0)
+        want = O.decode_attn(d_host["q"][l, b], kc, vc, scales[l])
+        assert_close(got[l, b], want, what=f"{what} step {step} b={b} l={l}", **out_tol(cfg))
+
+
+@pytest.mark.parametrize("unit", [128, 256, 512])
+@pytest.mark.parametrize("merge", [1, 2])
+@pytest.mark.parametrize("order", [1, 2])
+def test_rows_that_grow_across_a_unit_boundary_during_decode(unit, merge, order):
+    """Budgets of unit - 2 (and 2 * unit - 2, and a short row) with 6 appended tokens: on the third step a unit
+    that only held append reserve becomes live, the row goes from one unit to two (from two to three) and its
+    result from a direct store to a merge of partials.  Every step against the oracle, launches over all layers
+    and per layer, both merge forms, both orders of the work list."""
+    V = _V()
+    cfg = _small_cfg(cid=88, m=1200, n_visual=1100, L=3, B=2, Hq=8, Hkv=2)
+    kk = np.array([[unit - 2, 2 * unit - 2, 40], [unit - 2, 7, 2 * unit - 2]])
+    T = 6
+    for per_layer in (False, True):
+        opts = dict(unit_slots=unit, layer_unit_slots=unit, decode_merge=merge, decode_order=order)
+        path, dev, caches, scales = _direct_cache(V, cfg, kk, T, opts)
+        assert path.cache.layout.unit_slots == unit and path.cache.layout.layer_unit_slots == unit
+        out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=torch.bfloat16, device="cuda")
+        crossed = False
+        for step in range(T):
+            d_host = W.decode_step_inputs(cfg, step)
+            dd = {n: torch.from_numpy(x).to(torch.bfloat16).cuda() for n, x in d_host.items()}
+            if per_layer:
+                for l in range(cfg.L):
+                    path.decode(l, l + 1, dd["q"][l], dd["k_new"][l], dd["v_new"][l], dev["sm_scale"], out[l])
             else:
-                os.environ[k] = v
+                path.decode(0, cfg.L, dd["q"], dd["k_new"], dd["v_new"], dev["sm_scale"], out)
+            torch.cuda.synchronize()
+            _oracle_step(cfg, caches, scales, d_host, out.float().cpu().numpy(), step, f"unit={unit} per_layer={per_layer}")
+            crossed |= (unit - 2 + step + 1) > unit
+        assert crossed
+        path.status()
+
+
+@pytest.mark.parametrize("per_layer", [False, True], ids=["all-layers", "per-layer"])
+@pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
+def test_one_decode_step_replays_from_a_hip_graph(per_layer, fp8):
+    """The append count lives on the device: a HIP graph that holds ONE decode step (one call over all layers, or
+    one call per layer) is replayed T times, with the new q / k_new / v_new written into the same buffers before
+    each replay and eager work in between, and matches the oracle at every step.  One replay more than slots
+    were reserved attends without appending and raises the sticky capacity status."""
+    V = _V()
+    cfg = _small_cfg(cid=89, m=1400, n_visual=1300, L=3, B=2, Hq=8, Hkv=2)
+    kk = np.array([[254, 600, 30], [127, 1, 511]])           # rows that cross 128- and 256-slot boundaries while replaying
+    T = 7
+    path, dev, caches, scales = _direct_cache(V, cfg, kk, T, dict(kv_fp8=int(fp8)))
+    if fp8:
+        for key, (kc, vc) in caches.items():
+            caches[key] = ([O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(x)) for x in kc],
+                           [O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(x)) for x in vc])
+    bf = torch.bfloat16
+    q = torch.zeros((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=bf, device="cuda")
+    kn = torch.zeros((cfg.L, cfg.B, cfg.Hkv, cfg.d), dtype=bf, device="cuda")
+    vn = torch.zeros_like(kn)
+    out = torch.zeros_like(q)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        if per_layer:
+            for l in range(cfg.L):
+                path.decode(l, l + 1, q[l], kn[l], vn[l], dev["sm_scale"], out[l])
+        else:
+            path.decode(0, cfg.L, q, kn, vn, dev["sm_scale"], out)
+    lay = path.cache.layout
+    count = path.cache.arena[lay.appended_off: lay.appended_off + 4 * cfg.L].view(torch.int32)
+    assert count.tolist() == [0] * cfg.L, "capturing a step must not run it"
+    for step in range(T):
+        d_host = W.decode_step_inputs(cfg, step)
+        q.copy_(torch.from_numpy(d_host["q"]).to(bf)); kn.copy_(torch.from_numpy(d_host["k_new"]).to(bf))
+        vn.copy_(torch.from_numpy(d_host["v_new"]).to(bf))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert count.tolist() == [step + 1] * cfg.L
+        if fp8:
+            d_host = dict(d_host, k_new=O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(d_host["k_new"])),
+                          v_new=O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(d_host["v_new"])))
+        _oracle_step(cfg, caches, scales, d_host, out.float().cpu().numpy(), step, f"replay per_layer={per_layer}")
+    path.status()
+    # one step too many: nothing is appended, nothing is counted, the result is the attention over the full cache
+    before = out.clone()
+    q.copy_(torch.from_numpy(W.decode_step_inputs(cfg, T - 1)["q"]).to(bf))
+    graph.replay()
+    torch.cuda.synchronize()
+    assert count.tolist() == [T] * cfg.L
+    with pytest.raises(V.VlcError) as e:
+        path.status()
+    assert e.value.status == V.VLC_ERR_CAPACITY and "reserved" in str(e.value)
+    for (b, l), (kc, vc) in caches.items():
+        want = O.decode_attn(W.decode_step_inputs(cfg, T - 1)["q"][l, b], kc, vc, scales[l])
+        from gpu_util import assert_close, out_tol
+        assert_close(out[l, b].float().cpu().numpy(), want, what=f"over-capacity replay b={b} l={l}", **out_tol(cfg))
+    del before
 
 
 @pytest.mark.parametrize("attr,mutant", [("causal_valid", "_strict_mask"), ("logits", "_logits_interleaved_heads"),

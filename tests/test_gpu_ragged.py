@@ -32,13 +32,12 @@ def test_ragged_batch_matches_the_oracle_request_by_request(dtype, d, Hq, Hkv, L
     _ragged_case(dtype, d, Hq, Hkv, L, lens)
 
 
-def test_ragged_batch_with_the_layout_in_a_kernel_of_its_own(monkeypatch):
+def test_ragged_batch_with_the_layout_in_a_kernel_of_its_own():
     """The same comparison with the cache layout forced out of the selection kernel (the form large batches take)."""
-    monkeypatch.setenv("VLC_SELECT_FOLD", "0")
-    _ragged_case("bf16", 128, 8, 2, 3, [(900, 40), (333, 7), (1200, 64), (64, 64)])
+    _ragged_case("bf16", 128, 8, 2, 3, [(900, 40), (333, 7), (1200, 64), (64, 64)], options=dict(select_fold=1))
 
 
-def _ragged_case(dtype, d, Hq, Hkv, L, lens):
+def _ragged_case(dtype, d, Hq, Hkv, L, lens, options=None):
     import paper_2410_23317_amd as V
     from paper_2410_23317_amd.pipeline import VLCachePath, cache_layer_view
     cfgs = _requests(dtype, d, Hq, Hkv, L, lens, cid0=300)
@@ -60,7 +59,8 @@ def _ragged_case(dtype, d, Hq, Hkv, L, lens):
     lens_t = torch.tensor(lens, dtype=torch.int32, device="cuda")
     shape = V.make_shape(B, L, Hq, Hkv, d, m_max, tau_max, dtype, lens=lens_t)
     alpha, T = (1, 5), 3
-    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=T, want_idx=True, lens=lens_t)
+    path = VLCachePath(shape, alpha=alpha, p=0.01, T_max=T, want_idx=True, lens=lens_t,
+                       options=None if options is None else V.make_options(**options))
     path.row_max.fill_(123.0)
     path.compress(q_win, k, v, sm)
     path.status()
