@@ -230,10 +230,10 @@ vlc_status vlc_cache_create_fp8(const vlc_shape* shape, int32_t T_max, int64_t s
  * decode tolerance, and they are fixed for the cache's lifetime.
  *   kv_fp8            1: rows stored as E4M3 codes + per-row scale (vlc_cache_create_fp8)
  *   unit_slots        decode launches over ALL layers cut every cached row into block-units; slots of a unit
- *                     that lies wholly inside the kept rows: 128, 256, 512 or 1024
+ *                     that lies wholly inside the kept rows: 128, 256, 512, 1024 or 2048
  *   tail_unit_slots   slots of the units that hold the end of a row and the slots reserved for appends:
- *                     128, 256, 512 or 1024, not above unit_slots
- *   layer_unit_slots  slots per unit for launches over a layer range (how a model calls decode): 128, 256, 512
+ *                     128 .. 2048, not above unit_slots
+ *   layer_unit_slots  slots per unit for launches over a layer range (how a model calls decode): 128 .. 2048
  *   decode_order      1: launches over all layers walk the units layer by layer; 2: by size class (whole
  *                     units first, then row ends, then append reserve), so the blocks dispatched last are short
  *   decode_merge      1: the unit of a row that finishes last merges the row's partial results inside the
@@ -362,6 +362,16 @@ vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_
 vlc_status vlc_decode_attn_steps(vlc_cache* cache, int32_t layer_begin, int32_t layer_end, int32_t n_steps,
                                  const void* q, const void* k_new, const void* v_new,
                                  const float* sm_scale, void* out, vlc_stream stream);
+
+/*
+ * vlc_probe_read_stream -- measurement aid, not a step of the path: one kernel that reads `bytes` bytes of
+ * device memory once (16-byte loads, eight per lane in flight, `blocks` blocks of 256 threads each reading a
+ * contiguous share) and writes nothing.  The benchmark times it next to the decode launch, on a buffer of the
+ * same size, to state what a pure read stream reaches on the device at hand (paper Sec. 2.1: decoding is
+ * bound by the bytes of the cache it reads).  buf and bytes must be multiples of 16; sink is one uint32 of
+ * device memory (practically never written).
+ */
+vlc_status vlc_probe_read_stream(const void* buf, size_t bytes, uint32_t* sink, int32_t blocks, vlc_stream stream);
 
 #ifdef __cplusplus
 }

@@ -102,6 +102,8 @@ def _load() -> C.CDLL:
     lib.vlc_decode_attn.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.vlc_decode_attn_steps.restype = C.c_int
     lib.vlc_decode_attn_steps.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.vlc_probe_read_stream.restype = C.c_int
+    lib.vlc_probe_read_stream.argtypes = [vp, sz, vp, i32, vp]
     return lib
 
 
@@ -292,6 +294,10 @@ def vlc_cache_hit_rate(cache: Cache, scores_star, hits_out, rate_out) -> None:
 def vlc_decode_attn(cache: Cache, layer_begin, layer_end, q, k_new, v_new, sm_scale, out) -> None:
     _check(lib.vlc_decode_attn(cache.handle, int(layer_begin), int(layer_end), _ptr(q), _ptr(k_new), _ptr(v_new),
                                _ptr(sm_scale), _ptr(out), _stream()))
+
+
+def vlc_probe_read_stream(buf, sink, blocks) -> None:
+    _check(lib.vlc_probe_read_stream(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), int(blocks), _stream()))
 
 
 def vlc_decode_attn_steps(cache: Cache, layer_begin, layer_end, n_steps, q, k_new, v_new, sm_scale, out) -> None:

@@ -12,11 +12,14 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvlcache.so")
 
-SOURCES = ["api.hip", "score_simple.hip", "score_mfma.hip", "window_attn.hip", "allocate.hip", "topk_compact.hip", "decode.hip"]
+SOURCES = ["api.hip", "score_simple.hip", "score_mfma.hip", "window_attn.hip", "allocate.hip", "topk_compact.hip", "decode.hip", "probe.hip"]
 
 # packed fp32 VALU ops are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("VLC_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # one-lane atomics whose result is needed much later: do not let the compiler turn them into a wave-wide
+         # reduction that waits for the result at once
+         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

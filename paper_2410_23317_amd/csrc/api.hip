@@ -273,8 +273,8 @@ vlc_status vlc_allocate(const vlc_shape* shape, const uint64_t* nnz, int64_t alp
 struct ArenaPlan {
     vlc_cache_layout lay;
     vlc_cache_options opt;      // resolved
-    size_t items_off[2], layer_start_off[2], row_first_off[2], partials_off, counters_off, readers_off, lens_off;
-    int64_t cap[2];
+    size_t items_off[vlc::kNumLists], layer_start_off[vlc::kNumLists], row_first_off[vlc::kNumLists], partials_off, counters_off, readers_off, lens_off;
+    int64_t cap[vlc::kNumLists];
 };
 
 static bool one_of(int v, std::initializer_list<int> ok) {
@@ -302,9 +302,9 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     if (T_max < 0 || T_max > (1 << 24)) return fail(VLC_ERR_INVALID_ARG, "T_max = %d is out of range", T_max);
     if (sum_k_max < s->L || sum_k_max > (int64_t)s->L * s->m)
         return fail(VLC_ERR_INVALID_ARG, "sum_k_max = %lld is outside [L, L*m]", (long long)sum_k_max);
-    if (!one_of(o.unit_slots, {0, 128, 256, 512, 1024}) || !one_of(o.tail_unit_slots, {0, 128, 256, 512, 1024}) ||
-        !one_of(o.layer_unit_slots, {0, 128, 256, 512}))
-        return fail(VLC_ERR_INVALID_ARG, "options: unit sizes %d / %d / %d are not among 128, 256, 512 (1024)", o.unit_slots,
+    if (!one_of(o.unit_slots, {0, 128, 256, 512, 1024, 2048}) || !one_of(o.tail_unit_slots, {0, 128, 256, 512, 1024, 2048}) ||
+        !one_of(o.layer_unit_slots, {0, 128, 256, 512, 1024, 2048}))
+        return fail(VLC_ERR_INVALID_ARG, "options: unit sizes %d / %d / %d are not among 128, 256, 512, 1024, 2048", o.unit_slots,
                     o.tail_unit_slots, o.layer_unit_slots);
     if (!one_of(o.decode_order, {0, 1, 2}) || !one_of(o.decode_merge, {0, 1, 2}) || !one_of(o.decode_zigzag, {0, 1, 2, 3}) ||
         !one_of(o.gather_rows, {0, 16, 32, 64, 128}) || !one_of(o.select_fold, {0, 1, 2}))
@@ -324,20 +324,21 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     if (!o.tail_unit_slots) o.tail_unit_slots = o.unit_slots;
     if (o.tail_unit_slots > o.unit_slots)
         return fail(VLC_ERR_INVALID_ARG, "options: tail_unit_slots = %d exceeds unit_slots = %d", o.tail_unit_slots, o.unit_slots);
-    // launches over a layer range: units fine enough that one layer of the batch fills the chip
+    // launches over a layer range: units fine enough that one layer of the batch spreads over the chip (measured:
+    // 128 slots for rows of a few hundred slots, 256 beyond, where more units per row make the merge the longer wait)
     if (!o.layer_unit_slots) {
         const int64_t layer_slots = (int64_t)s->B * s->Hkv * mean_row;
-        o.layer_unit_slots = layer_slots / 128 <= 2048 ? 128 : (layer_slots / 256 <= 2048 ? 256 : 512);
+        o.layer_unit_slots = mean_row < 512 ? 128 : (layer_slots / 256 <= 2048 ? 256 : 512);
     }
     plan->cap[0] = list_capacity(s, T_max, spr, o.layer_unit_slots, o.layer_unit_slots);
     plan->cap[1] = list_capacity(s, T_max, spr, o.unit_slots, o.tail_unit_slots);
+    plan->cap[2] = list_capacity(s, T_max, spr, vlc::kGatherUnit, vlc::kGatherUnit);
     // a launch over all layers whose units are all resident at once (768 blocks fit the chip) gains nothing from the
     // size-class order, which only moves the units of a row apart
     if (!o.decode_order) o.decode_order = plan->cap[1] > 1536 ? 2 : 1;
     if (!o.decode_merge) o.decode_merge = 1;
     if (!o.decode_zigzag) o.decode_zigzag = 3;
     if (!o.gather_rows) o.gather_rows = 64;
-    if (o.gather_rows > o.layer_unit_slots) o.gather_rows = o.layer_unit_slots;
     {
         // The layout rides along as one more block of the selection while all rows are resident at once and short
         // (m <= 4096), which is where a one-block kernel and its launch gap show.  With more rows the LDS the
@@ -347,12 +348,12 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
         if (!o.select_fold) o.select_fold = (BL * s->Hkv <= 512 && short_rows) ? 2 : 1;
         if (o.select_fold == 2 && !short_rows) o.select_fold = 1;
     }
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < vlc::kNumLists; ++i)
         if (plan->cap[i] > (int64_t)1 << 30)
             return fail(VLC_ERR_SHAPE, "cache of %lld decode units: budgets plus reserved appends are too large", (long long)plan->cap[i]);
     plan->opt = o;
     const int g = s->Hq / s->Hkv;
-    const int64_t cap_max = plan->cap[0] > plan->cap[1] ? plan->cap[0] : plan->cap[1];
+    const int64_t cap_max = plan->cap[0] > plan->cap[1] ? plan->cap[0] : plan->cap[1];      // the gather's list leaves no partial results
     size_t off = 0;
     lay->status_off = off;      off = align_up(off + 4 * sizeof(int32_t), 256);
     lay->slot_off_off = off;    off = align_up(off + BL * sizeof(int64_t), 256);
@@ -361,14 +362,14 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     lay->kv_off = off;          off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * s->d * es, 256);
     lay->idx_off = off;         off = align_up(off + (size_t)s->B * spr * s->Hkv * sizeof(int32_t), 256);
     lay->scratch_off = off;
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < vlc::kNumLists; ++i) {
         plan->items_off[i] = off;        off = align_up(off + (size_t)plan->cap[i] * sizeof(vlc::WorkItem), 256);
         plan->layer_start_off[i] = off;  off = align_up(off + (size_t)(s->L + 2) * sizeof(int32_t), 256);
         plan->row_first_off[i] = off;    off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
     }
     plan->partials_off = off;     off = align_up(off + (size_t)cap_max * g * (s->d + 2) * sizeof(float), 256);
     plan->counters_off = off;     off = align_up(off + BL * s->Hkv * sizeof(int32_t), 256);
-    plan->readers_off = off;      off = align_up(off + (size_t)(s->L + 1) * sizeof(int32_t), 256);
+    plan->readers_off = off;      off = align_up(off + (size_t)(s->L + 1) * vlc::kReaderStride * sizeof(int32_t), 256);
     plan->lens_off = off;         off = align_up(off + (size_t)s->B * 2 * sizeof(int32_t), 256);
     lay->scale_off = off;
     if (fp8) off = align_up(off + (size_t)s->B * spr * 2 * s->Hkv * sizeof(float), 256);
@@ -419,13 +420,13 @@ static vlc_status cache_create_common(const char* who, const vlc_shape* shape, i
     c->dev.appended = (int32_t*)(c->arena + lay.appended_off);
     c->dev.kv = c->arena + lay.kv_off;
     c->dev.idx = (int32_t*)(c->arena + lay.idx_off);
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < vlc::kNumLists; ++i) {
         vlc::WorkList& wl = c->dev.list[i];
         wl.items = (vlc::WorkItem*)(c->arena + plan.items_off[i]);
         wl.layer_start = (int32_t*)(c->arena + plan.layer_start_off[i]);
         wl.row_first = (int32_t*)(c->arena + plan.row_first_off[i]);
-        wl.u_big = i == 0 ? plan.opt.layer_unit_slots : plan.opt.unit_slots;
-        wl.u_small = i == 0 ? plan.opt.layer_unit_slots : plan.opt.tail_unit_slots;
+        wl.u_big = i == 0 ? plan.opt.layer_unit_slots : (i == 1 ? plan.opt.unit_slots : vlc::kGatherUnit);
+        wl.u_small = i == 0 ? plan.opt.layer_unit_slots : (i == 1 ? plan.opt.tail_unit_slots : vlc::kGatherUnit);
         wl.by_size = i == 1 && plan.opt.decode_order == 2;
         wl.cap = (int32_t)plan.cap[i];
     }
@@ -558,6 +559,16 @@ vlc_status vlc_decode_attn(vlc_cache* cache, int32_t layer_begin, int32_t layer_
     if (e != hipSuccess) return hip_fail(e, "vlc_decode_attn");
     if (k_new)
         for (int l = layer_begin; l < layer_end; ++l) cache->appended[l] += 1;
+    return VLC_OK;
+}
+
+vlc_status vlc_probe_read_stream(const void* buf, size_t bytes, uint32_t* sink, int32_t blocks, vlc_stream stream) {
+    if (!buf || !sink) return fail(VLC_ERR_INVALID_ARG, "vlc_probe_read_stream: buf and sink must not be NULL");
+    if (bytes < 16 || (bytes & 15) != 0 || ((uintptr_t)buf & 15) != 0)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_probe_read_stream: %zu bytes at %p: size and address must be multiples of 16", bytes, buf);
+    if (blocks < 1 || blocks > (1 << 20)) return fail(VLC_ERR_INVALID_ARG, "vlc_probe_read_stream: blocks = %d", blocks);
+    const hipError_t e = vlc::launch_read_stream(buf, bytes, sink, blocks, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "vlc_probe_read_stream");
     return VLC_OK;
 }
 

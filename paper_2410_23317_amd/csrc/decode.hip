@@ -28,6 +28,7 @@
 // Every block takes a ticket (dev.readers) right after it has read the count; the block that holds the
 // last ticket of the launch knows that every other block has read the count and writes the new one.
 // A HIP graph that holds one decode step can therefore be replayed step after step.
+#include <stddef.h>
 #include <stdlib.h>
 
 #include <type_traits>
@@ -89,26 +90,37 @@ __device__ __forceinline__ int32_t add_agent(int32_t* p, int32_t v) {
 
 // Merge the nu partials (unnormalised output, running max, running sum) of one row; partials
 // of consecutive units of a row are consecutive.  COHERENT: read with device-scope loads.
-template <typename T, int D, int G, bool COHERENT>
+// The loads of up to eight partials are all issued before the first is used: a row's merge then
+// costs one round trip to memory per eight units instead of one per unit.
+template <typename T, int D, int G, bool COHERENT, int THREADS>
 __device__ __forceinline__ void merge_partials(const float* part, T* outp, int nu, int tid) {
     constexpr int DP = D + 2;
     constexpr int UNIT = G * DP;
-    for (int x = tid; x < G * D; x += 256) {
+    constexpr int BATCH = 8;
+    for (int x = tid; x < G * D; x += THREADS) {
         const int h = x / D, e = x % D;
         const float* ph = part + h * DP;
-        // online merge: one round trip of independent loads instead of a max pass and a sum pass
         float mt = -INFINITY, o = 0.f, lt = 0.f;
-        for (int s = 0; s < nu; ++s) {
-            const float* p = ph + (size_t)s * UNIT;
-            const float ms = COHERENT ? load_agent(p + D) : p[D];
-            const float ls = COHERENT ? load_agent(p + D + 1) : p[D + 1];
-            const float os = COHERENT ? load_agent(p + e) : p[e];
-            const float mn = fmaxf(mt, ms);
-            const float wo = (mt > -INFINITY) ? exp2_fast(mt - mn) : 0.f;
-            const float wn = (ms > -INFINITY) ? exp2_fast(ms - mn) : 0.f;
-            o = o * wo + os * wn;
-            lt = lt * wo + ls * wn;
-            mt = mn;
+        for (int s0 = 0; s0 < nu; s0 += BATCH) {
+            float ms[BATCH], ls[BATCH], os[BATCH];
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const float* p = ph + (size_t)min(s0 + j, nu - 1) * UNIT;      // past the end: the last partial again, ignored below
+                ms[j] = COHERENT ? load_agent(p + D) : p[D];
+                ls[j] = COHERENT ? load_agent(p + D + 1) : p[D + 1];
+                os[j] = COHERENT ? load_agent(p + e) : p[e];
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                if (s0 + j < nu) {
+                    const float mn = fmaxf(mt, ms[j]);
+                    const float wo = (mt > -INFINITY) ? exp2_fast(mt - mn) : 0.f;
+                    const float wn = (ms[j] > -INFINITY) ? exp2_fast(ms[j] - mn) : 0.f;
+                    o = o * wo + os[j] * wn;
+                    lt = lt * wo + ls[j] * wn;
+                    mt = mn;
+                }
+            }
         }
         Elem<T>::store(outp + x, o / lt);
     }
@@ -194,8 +206,13 @@ template <> struct IsBf16<bf16_t> { static constexpr bool value = true; };
 // expanded to bf16 (exactly) where they are consumed, the K scale multiplies the finished logit, the
 // V scale the probability before it is rounded to bf16.  Appends to such a cache are done by
 // append_fp8_kernel before this kernel runs.
+// Blocks of four waves, three per CU for up to four query heads per KV head (two where the accumulators need the
+// registers): the blocks of a CU overlap each other's start-up and merge phases.  One wide block per row (12 waves,
+// no merge across blocks) measured no faster: the row's loads then queue at a single CU's address path.
 template <typename T, int D, int G, bool Q8>
-__global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodeParams P) {
+__global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 : 2)) void decode_kernel(DecodeParams P) {
+    constexpr int NW = 4;                       // waves per block
+    constexpr int THREADS = NW * 64;
     constexpr bool BF = IsBf16<T>::value;
     static_assert(!Q8 || BF, "FP8 caches hold bf16 models");
     constexpr int EP = Elem<T>::kPer16B;        // elements in a 16-byte chunk
@@ -211,95 +228,108 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
     static_assert(G <= LPR, "one lane per head needed when parking logits");
     static_assert(NIT % 2 == 0, "P.V pairs consecutive loads");
 
-    __shared__ __align__(16) float sL[4][TK][GP];        // logits, then fp32 probabilities (fp32 path)
-    __shared__ __align__(16) uint32_t sPk[4][TK / 2][GP]; // bf16 probability pairs of loads (2i, 2i+1)
-    __shared__ float sMerge[4][G][DP];
+    __shared__ __align__(16) float sL[NW][TK][GP];        // logits, then fp32 probabilities (fp32 path)
+    __shared__ __align__(16) uint32_t sPk[NW][TK / 2][GP]; // bf16 probability pairs of loads (2i, 2i+1)
+    __shared__ float sMerge[NW][G][DP];
     __shared__ int sLast;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int sub = lane / LPR, c = lane % LPR;
     const int srow = lane >> 4, scol = lane & 15;
-    const WorkList wl = P.wl;
+    // The work list and its layer index were written by the compaction, in an earlier launch: they are constant
+    // while this kernel runs and are read as such, which puts their (block-uniform) loads on the scalar unit.
+    typedef const __attribute__((address_space(4))) int32_t* IndexPtr;
     // ---- what the whole launch shares: the slice of the list, and the append count of its layers
-    const int begin = P.layer_begin ? wl.layer_start[P.layer_begin] : 0;
-    const int end = wl.layer_start[P.layer_begin + P.n_layers];
+    const IndexPtr layer_start = (IndexPtr)P.wl.layer_start;
+    const int begin = P.layer_begin ? layer_start[P.layer_begin] : 0;
+    const int end = layer_start[P.layer_begin + P.n_layers];
     const int appended = P.dev.appended[P.layer_begin];
     int mode = P.append_mode;
-    if (mode && appended >= P.T_max) {          // more steps than slots were reserved (only a replayed graph gets here):
-        if (blockIdx.x == 0 && tid == 0) set_sticky(P.dev.status, VLC_ERR_CAPACITY, -3, P.layer_begin, appended);
-        mode = 0;                               // attend over what the cache holds, append nothing, count nothing
-    }
+    // more steps than slots were reserved (only a replayed graph gets here): attend over what the cache holds,
+    // append nothing, count nothing, and report it (after the block's first unit: a store in front of the unit
+    // record's load would keep that load off the scalar unit)
+    const bool over = mode && appended >= P.T_max;
+    if (over) mode = 0;
     const bool appending = mode == 1;
     const int step = appended + (mode ? 1 : 0); // appends the cache holds once this launch is done
     // A block takes its ticket only after it has read the append count: the operand of the ticket's atomic add
     // is produced by a statement that consumes the count.
     int one = 1;
     asm volatile("" : "+s"(one) : "s"(appended));
-    // The block that holds the last ticket of its layer, and then of the launch, publishes the new count.
-    auto finish = [&](int ticket, int il) {
-        const int n_layer = wl.layer_start[il + 1] - wl.layer_start[il];
-        if (ticket != n_layer - 1) return;
-        store_agent(P.dev.readers + il, 0);
-        if (P.n_layers > 1) {
-            if (add_agent(P.dev.readers + P.L, 1) != P.n_layers - 1) return;
-            store_agent(P.dev.readers + P.L, 0);
-        }
-        for (int l = P.layer_begin; l < P.layer_begin + P.n_layers; ++l) store_agent(P.dev.appended + l, step);
-    };
     // One block-unit per block while the grid covers the slice (the hardware dispatcher then balances the ragged
-    // units); a capped grid walks the rest of the slice with the grid as stride.  The grid is a host-side upper
-    // bound on the units of the layer range, surplus blocks leave below.
-#pragma unroll 1
-    for (int w0 = blockIdx.x;; w0 += gridDim.x) {
+    // units); a capped grid walks the rest of the slice with the grid as stride (below).  The grid is a host-side
+    // upper bound on the units of the layer range, surplus blocks leave at once.  Returns false past the slice.
+    // A is the parameter struct: the kernel's own copy for a block's first unit, a view of the kernel-argument
+    // memory that the compiler cannot see through for further units (see below).
+    auto process_unit = [&](auto firstc, const auto& A, int w0) -> bool {
+        constexpr bool FIRST = decltype(firstc)::value;
+        // The block that holds the last ticket of its layer, and then of the launch, publishes the new count.
+        auto finish = [&](int ticket, int il, int n_layer) {
+            if (ticket != n_layer - 1) return;
+            store_agent(A.dev.readers + il * kReaderStride, 0);
+            if (A.n_layers > 1) {
+                if (add_agent(A.dev.readers + A.L * kReaderStride, 1) != A.n_layers - 1) return;
+                store_agent(A.dev.readers + A.L * kReaderStride, 0);
+            }
+            for (int l = A.layer_begin; l < A.layer_begin + A.n_layers; ++l) store_agent(A.dev.appended + l, step);
+        };
         int w = w0;
-        if (wl.by_size && P.zigzag > 2 && (step & 1)) {   // size-class order, odd step: the whole units are walked backwards, so that
-            const int nf = min(wl.layer_start[P.L + 1], (int)gridDim.x);   // what the memory-side cache kept of the last step comes first
+        if (A.wl.by_size && A.zigzag > 2 && (step & 1)) {   // size-class order, odd step: the whole units are walked backwards, so that
+            const int nf = min(((IndexPtr)A.wl.layer_start)[A.L + 1], (int)gridDim.x);   // what the memory-side cache kept of the last step comes first
             const int nf8 = nf & ~7;            // whole groups of 8 change places, so a unit stays on its XCD (and its L2)
             if (w < nf8) w = nf8 - 8 - (w & ~7) + (w & 7);
         }
         w += begin;
-        if (w >= wl.cap) break;
-        const WorkItem itv = wl.items[w];       // requested together with the bounds of the slice
-        if (w >= end) break;
-        if (w0 != (int)blockIdx.x) __syncthreads();       // the previous unit's merge buffers are free again
-        const int kept = uniform(itv.kept), key0 = uniform(itv.key0), row_abs = uniform(itv.row_abs);
-        const int unit = uniform(itv.unit), ib = uniform(itv.b), il = uniform(itv.l), canon = uniform(itv.canon);
-        const int ucap = uniform(itv.ucap);
-        const int64_t kbase = uniform64(itv.kbase), idx_base = uniform64(itv.idx_base);
-        const int lr = il - P.layer_begin;
-        const int hkv = row_abs - (ib * P.L + il) * P.Hkv;
-        int ticket = -1;
-        if (mode && tid == 0) ticket = add_agent(P.dev.readers + il, one);
-        T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + ib) * P.Hq + (size_t)hkv * G) * D;
+        if (!FIRST && w >= end) return false;
+        if (w >= A.wl.cap) return false;
+        // the unit record, word by word (a block's first unit: requested together with the bounds of the slice)
+        static_assert(offsetof(WorkItem, row_abs) == 0 && offsetof(WorkItem, key0) == 4 && offsetof(WorkItem, kept) == 8 &&
+                      offsetof(WorkItem, unit) == 12 && offsetof(WorkItem, kbase) == 16 && offsetof(WorkItem, idx_base) == 24 &&
+                      offsetof(WorkItem, b) == 32 && offsetof(WorkItem, l) == 36 && offsetof(WorkItem, canon) == 40 &&
+                      offsetof(WorkItem, ucap) == 44 && offsetof(WorkItem, hkv) == 48 && offsetof(WorkItem, layer_units) == 52,
+                      "the record is read as 16 words");
+        const IndexPtr rec = (IndexPtr)(A.wl.items + w);
+        const int row_abs = rec[0], key0 = rec[1], kept = rec[2], unit = rec[3];
+        const int64_t kbase = (int64_t)(((uint64_t)(uint32_t)rec[5] << 32) | (uint32_t)rec[4]);
+        const int64_t idx_base = (int64_t)(((uint64_t)(uint32_t)rec[7] << 32) | (uint32_t)rec[6]);
+        const int ib = rec[8], il = rec[9], canon = rec[10], ucap = rec[11], hkv = rec[12], n_layer = rec[13];
+        if (w >= end) return false;
+        const int lr = il - A.layer_begin;
+        // The ticket: taken at once by a unit that has nothing to read, else behind the loads of the unit's first
+        // tile (returns come back in issue order: in front of them it would hold up the first tile).
+        auto take_ticket = [&]() { return (mode && tid == 0) ? add_agent(A.dev.readers + il * kReaderStride, one) : -1; };
+        T* outp = reinterpret_cast<T*>(A.out) + ((size_t)(lr * A.B + ib) * A.Hq + (size_t)hkv * G) * D;
         if (kept == 0) {                        // request rejected at compaction: defined output, no reads
-            for (int x = tid; x < G * D; x += 256) Elem<T>::store(outp + x, 0.f);
-            if (mode && tid == 0) finish(ticket, il);
-            continue;
+            const int ticket = take_ticket();
+            for (int x = tid; x < G * D; x += THREADS) Elem<T>::store(outp + x, 0.f);
+            if (mode && tid == 0) finish(ticket, il, n_layer);
+            return true;
         }
         const int len = kept + step;
         if (key0 >= len) {                      // unit reserved for later appends
-            if (mode && tid == 0) finish(ticket, il);
-            continue;
+            const int ticket = take_ticket();
+            if (mode && tid == 0) finish(ticket, il, n_layer);
+            return true;
         }
-        const int nbig = kept >> P.ub_shift;    // units of this row that hold slots now: the whole ones, and the small ones up to len
-        const int nu = nbig + ((len - (nbig << P.ub_shift) + (1 << P.us_shift) - 1) >> P.us_shift);
-        const int cap = kept + P.T_max;
+        const int nbig = kept >> A.ub_shift;    // units of this row that hold slots now: the whole ones, and the small ones up to len
+        const int nu = nbig + ((len - (nbig << A.ub_shift) + (1 << A.us_shift) - 1) >> A.us_shift);
+        const int cap = kept + A.T_max;
         const int new_slot = appending ? len - 1 : -1;
-        const T* Kbase = reinterpret_cast<const T*>(P.dev.kv) + kbase;
-        const T* Vbase = Kbase + (int64_t)P.Hkv * cap * D;
-        const uint8_t* K8 = reinterpret_cast<const uint8_t*>(P.dev.kv) + kbase;      // FP8 cache: one byte per element
-        const uint8_t* V8 = K8 + (int64_t)P.Hkv * cap * D;
-        const float* Ksc = P.dev.scales + kbase / D;
-        const float* Vsc = Ksc + (int64_t)P.Hkv * cap;
-        const T* knew = reinterpret_cast<const T*>(P.k_new) + ((size_t)(lr * P.B + ib) * P.Hkv + hkv) * D;
-        const T* vnew = reinterpret_cast<const T*>(P.v_new) + ((size_t)(lr * P.B + ib) * P.Hkv + hkv) * D;
-        const float scale2 = (P.sm_scale ? P.sm_scale[il] : P.default_scale) * kLog2e;
+        const T* Kbase = reinterpret_cast<const T*>(A.dev.kv) + kbase;
+        const T* Vbase = Kbase + (int64_t)A.Hkv * cap * D;
+        const uint8_t* K8 = reinterpret_cast<const uint8_t*>(A.dev.kv) + kbase;      // FP8 cache: one byte per element
+        const uint8_t* V8 = K8 + (int64_t)A.Hkv * cap * D;
+        const float* Ksc = A.dev.scales + kbase / D;
+        const float* Vsc = Ksc + (int64_t)A.Hkv * cap;
+        const T* knew = reinterpret_cast<const T*>(A.k_new) + ((size_t)(lr * A.B + ib) * A.Hkv + hkv) * D;
+        const T* vnew = reinterpret_cast<const T*>(A.v_new) + ((size_t)(lr * A.B + ib) * A.Hkv + hkv) * D;
+        const float scale2 = (A.sm_scale ? A.sm_scale[il] : A.default_scale) * kLog2e;
 
         uint4 qv[G];
 #pragma unroll
         for (int h = 0; h < G; ++h)
-            qv[h] = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(P.q) +
-                                                    ((size_t)(lr * P.B + ib) * P.Hq + (size_t)hkv * G + h) * D + c * EP);
+            qv[h] = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(A.q) +
+                                                    ((size_t)(lr * A.B + ib) * A.Hq + (size_t)hkv * G + h) * D + c * EP);
 
         // running max / sum live per 16-lane row: row r owns heads r*HR .. r*HR + HR - 1
         float m_run[HR], l_run[HR], acc[G][EP];
@@ -481,12 +511,14 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
         // A wave walks its tiles forwards on even steps and backwards on odd ones: a cache that is a little
         // larger than an L2 then finds the tiles it touched last in the previous step first in this one.
         const int tw0 = key0 + wave * TK;
-        const int nt_w = tw0 < len ? min(ucap / (4 * TK), (len - tw0 + 4 * TK - 1) / (4 * TK)) : 0;     // tiles of this wave that hold slots
-        const bool rev = P.zigzag > 1 && (step & 1);
-        if (nt_w > 0) { const int t0 = tw0 + (rev ? nt_w - 1 : 0) * 4 * TK; issue_k(t0); issue_v(t0); }
+        const int lim = min(len, key0 + ucap);                                  // end of the unit's live slots
+        const int nt_w = tw0 < lim ? (lim - tw0 + NW * TK - 1) / (NW * TK) : 0;    // tiles of this wave that hold slots
+        const bool rev = A.zigzag > 1 && (step & 1);
+        if (nt_w > 0) { const int t0 = tw0 + (rev ? nt_w - 1 : 0) * NW * TK; issue_k(t0); issue_v(t0); }
+        const int ticket = take_ticket();
 #pragma unroll 1
         for (int i = 0; i < nt_w; ++i) {
-            const int t0 = tw0 + (rev ? nt_w - 1 - i : i) * 4 * TK;
+            const int t0 = tw0 + (rev ? nt_w - 1 - i : i) * NW * TK;
             if (i > 0) { issue_k(t0); issue_v(t0); }
             const bool full = (t0 + TK <= len);
             if (full) tile_body(std::true_type{}, t0); else tile_body(std::false_type{}, t0);
@@ -498,7 +530,7 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
             T* vdst = const_cast<T*>(Vbase) + (int64_t)new_slot * D;
             *reinterpret_cast<uint4*>(kdst + c * EP) = *reinterpret_cast<const uint4*>(knew + c * EP);
             *reinterpret_cast<uint4*>(vdst + c * EP) = *reinterpret_cast<const uint4*>(vnew + c * EP);
-            if (c == 0) P.dev.idx[idx_base + new_slot] = P.m + appended;
+            if (c == 0) A.dev.idx[idx_base + new_slot] = A.m + appended;
         }
 
         // ---- sum the row groups of the wave, then merge the 4 waves through LDS
@@ -524,15 +556,15 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
                 }
         }
         __syncthreads();
-        float* part = P.dev.partials + (size_t)canon * G * DP;      // partials sit in the layer-major order
-        for (int x = tid; x < G * D; x += 256) {
+        float* part = A.dev.partials + (size_t)canon * G * DP;      // partials sit in the layer-major order
+        for (int x = tid; x < G * D; x += THREADS) {
             const int h = x / D, e = x % D;
             float mt = -INFINITY;
 #pragma unroll
-            for (int wv = 0; wv < 4; ++wv) mt = fmaxf(mt, sMerge[wv][h][D]);
+            for (int wv = 0; wv < NW; ++wv) mt = fmaxf(mt, sMerge[wv][h][D]);
             float o = 0.f, lt = 0.f;
 #pragma unroll
-            for (int wv = 0; wv < 4; ++wv) {
+            for (int wv = 0; wv < NW; ++wv) {
                 const float mw = sMerge[wv][h][D];
                 const float wgt = (mw > -INFINITY) ? exp2_fast(mw - mt) : 0.f;
                 o = fmaf(sMerge[wv][h][e], wgt, o);
@@ -540,7 +572,7 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
             }
             if (nu == 1) {
                 Elem<T>::store(outp + x, o / lt);
-            } else if (P.merge_mode == 1) {
+            } else if (A.merge_mode == 1) {
                 store_agent(part + h * DP + e, o);
                 if (e == 0) { store_agent(part + h * DP + D, mt); store_agent(part + h * DP + D + 1, lt); }
             } else {
@@ -548,7 +580,7 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
                 if (e == 0) { part[h * DP + D] = mt; part[h * DP + D + 1] = lt; }
             }
         }
-        if (nu > 1 && P.merge_mode == 1) {
+        if (nu > 1 && A.merge_mode == 1) {
             // Publication of the partials.  They were written with device-scope stores, which go through to the
             // memory side of the XCDs' L2 caches.  Every thread first waits until its own stores have been
             // acknowledged (a workgroup barrier alone does not drain another wave's outstanding stores), then
@@ -557,15 +589,33 @@ __global__ __launch_bounds__(256, (G <= 4 ? 3 : 2)) void decode_kernel(DecodePar
             // memory; it reads them with device-scope loads, which do not hit a stale line of its own L2.
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            int32_t* counter = P.dev.counters + row_abs;
+            int32_t* counter = A.dev.counters + row_abs;
             if (tid == 0) sLast = (add_agent(counter, 1) == nu - 1) ? 1 : 0;
             __syncthreads();
             if (sLast) {
-                merge_partials<T, D, G, true>(P.dev.partials + (size_t)(canon - unit) * G * DP, outp, nu, tid);
+                merge_partials<T, D, G, true, THREADS>(A.dev.partials + (size_t)(canon - unit) * G * DP, outp, nu, tid);
                 if (tid == 0) store_agent(counter, 0);
             }
         }
-        if (mode && tid == 0) finish(ticket, il);
+        if (mode && tid == 0) finish(ticket, il, n_layer);
+        return true;
+    };
+    const bool more = process_unit(std::true_type{}, P, (int)blockIdx.x);
+    if (over && blockIdx.x == 0 && tid == 0) set_sticky(P.dev.status, VLC_ERR_CAPACITY, -3, P.layer_begin, appended);
+    if (!more) return;
+    // A launch over a layer range runs at most one resident round of blocks, whatever the budgets turn out to be;
+    // units beyond the grid are taken here, with the grid as stride.  Code inside a loop compiles worse (loop
+    // invariants are hoisted and held in registers, which spills here), so a block's first unit, which is all
+    // there is unless a layer range holds more units than the grid, stays outside the loop, and inside it the
+    // parameters are read where they are used, through a copy of the kernel-argument pointer that the compiler
+    // cannot see through.
+    typedef const __attribute__((address_space(4))) DecodeParams* ParamsPtr;
+#pragma unroll 1
+    for (int w0 = (int)blockIdx.x + (int)gridDim.x;; w0 += (int)gridDim.x) {
+        ParamsPtr Q = (ParamsPtr)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(Q));
+        __syncthreads();                        // the previous unit's merge buffers are free again
+        if (!process_unit(std::false_type{}, *Q, w0)) break;
     }
 }
 
@@ -617,7 +667,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams P) {
     if (nu == 1) return;
     T* outp = reinterpret_cast<T*>(P.out) + ((size_t)(lr * P.B + b) * P.Hq + (size_t)hkv * G) * D;
     const int w0 = P.wl.row_first[(size_t)bl * P.Hkv + hkv];
-    merge_partials<T, D, G, false>(P.dev.partials + (size_t)w0 * G * (D + 2), outp, nu, threadIdx.x);
+    merge_partials<T, D, G, false, 256>(P.dev.partials + (size_t)w0 * G * (D + 2), outp, nu, threadIdx.x);
 }
 
 template <typename T, int D, int G>

@@ -12,12 +12,15 @@ namespace vlc {
 
 constexpr int kMaxLayers = 1024;
 constexpr int kScoreChunk = 256;       // keys per block of the generic scoring sweeps
+constexpr int kReaderStride = 64;      // ints between the ticket counters of two layers: a cache line each (measured: counters that share a
+                                       // line cost a launch over all layers of the 7B shape 1.7 of 16 us)
 
 // One block-unit of decode work: consecutive cache slots [key0, key0 + ucap) of one (b, l, kv head) row.
 // vlc_topk_compact builds two lists of them on the device.  A row is cut into floor(kept / u_big) units of
 // u_big slots followed by units of u_small slots that hold the end of the row and the append reserve.
 //   list 0 (launches over a layer range): ordered by (layer, request, kv head, unit), so that a layer
-//           range is a contiguous slice; also drives the gather;
+//           range is a contiguous slice;
+//   list 2 (the gather of the compaction): the same order, uniform fine units;
 //   list 1 (launches over all layers): the same order, or by size class (all u_big units, then the small
 //           units that hold kept rows, then the units that only hold append reserve), so that the blocks
 //           dispatched last are the short ones.
@@ -31,8 +34,14 @@ struct WorkItem {
     int32_t b, l;
     int32_t canon;                     // index of this unit in the (layer, request, kv head, unit) order of its list
     int32_t ucap;                      // slots of the unit
+    int32_t hkv;                       // the row's KV head
+    int32_t layer_units;               // units of layer l in this list (every one of them takes a ticket in a launch that appends)
+    int32_t pad[2];
 };
-static_assert(sizeof(WorkItem) == 48, "WorkItem layout");
+static_assert(sizeof(WorkItem) == 64, "WorkItem layout: one 64-byte scalar load");
+
+constexpr int kNumLists = 3;
+constexpr int kGatherUnit = 256;        // slots per unit of the gather's list
 
 struct WorkList {
     WorkItem* items;                   // [cap]
@@ -49,11 +58,11 @@ struct CacheDev {                      // device pointers into the caller's aren
     int32_t* kept;                     // [B*L]
     char* kv;
     int32_t* idx;
-    WorkList list[2];
+    WorkList list[kNumLists];         // 0: launches over a layer range, 1: launches over all layers, 2: the gather
     float* partials;                   // [max list cap][g][d + 2]
     int32_t* counters;                 // [B*L*Hkv] units of a row that have left their partial result
     int32_t* appended;                 // [L] appends each layer has received since the last compaction
-    int32_t* readers;                  // [L + 1] blocks of a launch that have read the append count: per layer, [L] per launch
+    int32_t* readers;                  // [(L + 1) * kReaderStride] blocks of a launch that have read the append count: per layer, and per launch after the last layer
     int32_t* lens;                     // [B][2] copy of the per-request (m_b, tau_b) of the last compaction
     float* scales;                     // FP8 caches: one fp32 scale per K row and per V row, laid out like the rows
 };
@@ -145,5 +154,8 @@ struct DecodeArgs {
     hipStream_t stream;
 };
 hipError_t launch_decode(const DecodeArgs& a);
+
+// ---- measurement aid: a kernel that only reads `bytes` bytes (a multiple of 16) once
+hipError_t launch_read_stream(const void* buf, size_t bytes, uint32_t* sink, int blocks, hipStream_t st);
 
 }  // namespace vlc

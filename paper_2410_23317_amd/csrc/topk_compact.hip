@@ -73,7 +73,7 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
     }
     for (int x = tid; x < BL * Hkv; x += NT) dev.counters[x] = 0;
     for (int x = tid; x < L; x += NT) dev.appended[x] = 0;          // decode starts at step 0
-    for (int x = tid; x <= L; x += NT) dev.readers[x] = 0;
+    for (int x = tid; x <= L; x += NT) dev.readers[x * kReaderStride] = 0;
     __syncthreads();
     // slab offsets, one thread per request; a request whose budgets do not fit keeps nothing
     for (int b = tid; b < B; b += NT) {
@@ -93,12 +93,12 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
         dev.kept[x] = sKept[x];
         dev.slot_off[x] = sSlot[x];
     }
-    // The two work lists.  Units per row, exclusive prefix over (layer, request) in that order, for all units
+    // The work lists.  Units per row, exclusive prefix over (layer, request) in that order, for all units
     // and separately for the u_big units and the live small ones (the size-class order).  Each thread sums
     // a run of consecutive entries, the run totals are scanned across the block, then every thread
     // walks its run again from its offset.
 #pragma unroll 1
-    for (int li = 0; li < 2; ++li) {
+    for (int li = 0; li < kNumLists; ++li) {
         const WorkList wl = dev.list[li];
         const int ub = wl.u_big, us = wl.u_small;
         __syncthreads();                        // the staging arrays of the previous list are no longer read
@@ -156,7 +156,8 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
             const int cap = kk + T_max;
             const int64_t so = sSlot[bl];
             WorkItem it;
-            it.row_abs = x; it.kept = kk; it.b = b; it.l = l;
+            it.row_abs = x; it.kept = kk; it.b = b; it.l = l; it.hkv = h; it.pad[0] = 0; it.pad[1] = 0;
+            it.layer_units = (l + 1 < L ? sFirst[l + 1] : (int)total) - sFirst[l];      // request 0 starts each layer
             it.kbase = ((so * 2 * Hkv) + (int64_t)h * cap) * d;
             it.idx_base = so * Hkv + (int64_t)h * cap;
             const int w0 = sFirst[bl] + h * ru.total;
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     }
 }
 
-// `parts` blocks per unit of the layer-major work list (up to u rows of one (request, layer, KV head) row),
+// `parts` blocks per unit of the gather's work list (up to kGatherUnit rows of one (request, layer, KV head) row),
 // each moving an equal share of it.  The grid is a multiple of the list's capacity, so it
 // follows the budgets that fit the arena rather than rows * m, and surplus blocks leave after two loads.  Each lane moves 16 bytes of one K row and
 // one V row per pass; the position of the next row is fetched before the stores are issued.  More
@@ -464,7 +465,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const char* __restrict__ k_
                                                      int elem_bytes, int parts) {
     constexpr int LPR = ROWBYTES / 16;          // lanes per row
     constexpr int RPB = 256 / LPR;              // rows per block pass
-    const WorkList wl = dev.list[0];
+    const WorkList wl = dev.list[2];
     const int w = blockIdx.x / parts, part = blockIdx.x % parts;
     const WorkItem it = wl.items[w];            // the grid never exceeds the list's capacity
     if (w >= wl.layer_start[L]) return;
@@ -499,7 +500,7 @@ __global__ __launch_bounds__(256) void gather_fp8_kernel(const char* __restrict_
                                                          CacheDev dev, int L, int Hkv, int m, int T_max) {
     constexpr int LPR = D / 8;                  // lanes per row: 8 bf16 values (16 bytes) each
     constexpr int RPB = 256 / LPR;
-    const WorkList wl = dev.list[0];
+    const WorkList wl = dev.list[2];
     const int w = blockIdx.x;
     const WorkItem it = wl.items[w];
     if (w >= wl.layer_start[L]) return;
@@ -555,7 +556,7 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
 #undef VLC_SELECT
     const int rowbytes = s.d * (s.dtype == VLC_F32 ? 4 : 2);
     const int es = s.dtype == VLC_F32 ? 4 : 2;
-    const unsigned grid = (unsigned)c.dev.list[0].cap;
+    const unsigned grid = (unsigned)c.dev.list[2].cap;
     const char* kf = (const char*)k_full;
     const char* vf = (const char*)v_full;
     if (c.kv_fp8) {
@@ -565,7 +566,7 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
     }
     // Several blocks share a unit: more, shorter chains of dependent passes in flight (64 rows per block measured
     // 3-7 % faster on the whole compaction than 512).
-    const int parts = c.opt.layer_unit_slots / c.opt.gather_rows;
+    const int parts = kGatherUnit / c.opt.gather_rows;
     const unsigned g2 = grid * (unsigned)parts;
     if (rowbytes == 128) gather_kernel<128><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, es, parts);
     else if (rowbytes == 256) gather_kernel<256><<<g2, 256, 0, st>>>(kf, vf, c.dev, s.L, s.Hkv, s.m, c.T_max, es, parts);

@@ -170,15 +170,24 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
     dt = torch_dtype(cfg)
     out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device="cuda")
     if steps_entry_point and n_steps:
-        hosts = [W.decode_step_inputs(cfg, t) for t in range(n_steps)]
-        stack = {n: torch.from_numpy(np.stack([h[n] for h in hosts])).to(dt).cuda() for n in ("q", "k_new", "v_new")}
+        # every step's inputs go to the GPU first (the host keeps only the layers it will check), then ONE call
+        # enqueues all steps, as the benchmark does
+        stack = {"q": torch.empty((n_steps, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device="cuda"),
+                 "k_new": torch.empty((n_steps, cfg.L, cfg.B, cfg.Hkv, cfg.d), dtype=dt, device="cuda")}
+        stack["v_new"] = torch.empty_like(stack["k_new"])
+        hosts = []
+        for t in range(n_steps):
+            d = W.decode_step_inputs(cfg, t)
+            for n in stack:
+                stack[n][t].copy_(torch.from_numpy(d[n]).to(dt))
+            hosts.append({n: {l: d[n][l] for l in lays} for n in d})
         out_all = torch.empty((n_steps, cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=dt, device="cuda")
         path.decode_steps(0, cfg.L, n_steps, stack["q"], stack["k_new"], stack["v_new"], dev["sm_scale"], out_all)
         torch.cuda.synchronize()
-        out_all = out_all.float().cpu().numpy()
     for step in range(n_steps):
         if steps_entry_point:
-            d_host, got = hosts[step], out_all[step]
+            d_host = hosts[step]
+            got = {l: out_all[step, l].float().cpu().numpy() for l in lays}
         else:
             d_dev, d_host = decode_upload(cfg, step)
             if per_layer_decode:
@@ -190,10 +199,10 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
             got = out.float().cpu().numpy()
         for (b, l), (kc, vc) in caches.items():
             for h in range(cfg.Hkv):
-                kc[h] = np.concatenate([kc[h], d_host["k_new"][l, b, h][None]], 0)
-                vc[h] = np.concatenate([vc[h], d_host["v_new"][l, b, h][None]], 0)
-            want = O.decode_attn(d_host["q"][l, b], kc, vc, scales[l])
-            assert_close(got[l, b], want, what=f"{cfg.name} decode step {step} b={b} l={l}", **out_tol(cfg))
+                kc[h] = np.concatenate([kc[h], d_host["k_new"][l][b, h][None]], 0)
+                vc[h] = np.concatenate([vc[h], d_host["v_new"][l][b, h][None]], 0)
+            want = O.decode_attn(d_host["q"][l][b], kc, vc, scales[l])
+            assert_close(got[l][b], want, what=f"{cfg.name} decode step {step} b={b} l={l}", **out_tol(cfg))
     path.status()
     # the cache now holds the appended rows too
     if n_steps:

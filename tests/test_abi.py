@@ -136,7 +136,7 @@ def test_cache_options_are_validated_and_reported(V):
     assert V.vlc_cache_bytes(s, 100, sum_k) == V.vlc_cache_bytes_opt(s, 100, sum_k, None)     # NULL options = the defaults
     assert create(unit_slots=1024, tail_unit_slots=128, layer_unit_slots=256) == (1024, 128, 256)
     assert create(unit_slots=128) == (128, 128, default[2])
-    for bad in (dict(unit_slots=100), dict(unit_slots=128, tail_unit_slots=256), dict(layer_unit_slots=1024), dict(decode_merge=3),
+    for bad in (dict(unit_slots=100), dict(unit_slots=128, tail_unit_slots=256), dict(layer_unit_slots=4096), dict(gather_rows=256), dict(decode_merge=3),
                 dict(decode_order=-1), dict(decode_zigzag=4), dict(gather_rows=48), dict(select_fold=3), dict(kv_fp8=2)):
         assert create(**bad) is None, bad
         assert "options" in V.vlc_last_error_string()
