@@ -430,6 +430,11 @@ static vlc_status cache_create_common(const char* who, const vlc_shape* shape, i
         wl.by_size = i == 1 && plan.opt.decode_order == 2;
         wl.cap = (int32_t)plan.cap[i];
     }
+    // the gather walks uniform 256-slot units in layer order: a decode list of that very form serves it too
+    for (int i = 1; i >= 0; --i) {
+        const vlc::WorkList& wl = c->dev.list[i];
+        if (wl.u_big == vlc::kGatherUnit && wl.u_small == vlc::kGatherUnit && !wl.by_size) c->dev.list[2] = wl;
+    }
     c->dev.partials = (float*)(c->arena + plan.partials_off);
     c->dev.counters = (int32_t*)(c->arena + plan.counters_off);
     c->dev.readers = (int32_t*)(c->arena + plan.readers_off);

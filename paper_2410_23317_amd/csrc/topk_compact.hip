@@ -97,9 +97,8 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
     // and separately for the u_big units and the live small ones (the size-class order).  Each thread sums
     // a run of consecutive entries, the run totals are scanned across the block, then every thread
     // walks its run again from its offset.
-#pragma unroll 1
-    for (int li = 0; li < kNumLists; ++li) {
-        const WorkList wl = dev.list[li];
+    // (one instance of the code per list, so that each list's description stays in scalar registers)
+    auto build_list = [&](const WorkList& wl) {
         const int ub = wl.u_big, us = wl.u_small;
         __syncthreads();                        // the staging arrays of the previous list are no longer read
         if (tid == 0) sBad = 0;
@@ -111,19 +110,23 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
             run += (int64_t)ru.total * Hkv;
             run2 += ((int64_t)ru.big * Hkv << 32) | (int64_t)(ru.live * Hkv);
         }
-        sScan[tid] = run;
-        sScan2[tid] = run2;
-        __syncthreads();
-        for (int o = 1; o < NT; o <<= 1) {
-            const int64_t v = tid >= o ? sScan[tid - o] : 0;
-            const int64_t v2 = tid >= o ? sScan2[tid - o] : 0;
-            __syncthreads();
-            sScan[tid] += v;
-            sScan2[tid] += v2;
-            __syncthreads();
+        // inclusive scan of the run totals: inside each wave with lane shifts, then across the waves through LDS
+        int64_t inc = run, inc2 = run2;
+        const int lane = tid & 63, wv = tid >> 6;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int64_t v = (int64_t)__shfl_up((long long)inc, o, 64), v2 = (int64_t)__shfl_up((long long)inc2, o, 64);
+            if (lane >= o) { inc += v; inc2 += v2; }
         }
-        const int64_t total = sScan[NT - 1];
-        if (tid == 0) { sTotals[0] = (int)(sScan2[NT - 1] >> 32); sTotals[1] = (int)(sScan2[NT - 1] & 0xffffffff); }
+        if (lane == 63) { sScan[wv] = inc; sScan2[wv] = inc2; }
+        __syncthreads();
+        int64_t total = 0, total2 = 0;
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) {
+            const int64_t t = sScan[w], t2 = sScan2[w];
+            if (w < wv) { inc += t; inc2 += t2; }
+            total += t; total2 += t2;
+        }
+        if (tid == 0) { sTotals[0] = (int)(total2 >> 32); sTotals[1] = (int)(total2 & 0xffffffff); }
         if (total > wl.cap) {                   // cannot happen for budgets that passed the capacity check
             if (tid == 0) {
                 set_sticky(dev.status, VLC_ERR_CAPACITY, -1, -1, -1);
@@ -131,7 +134,7 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
             }
             for (int l = tid; l <= L + 1; l += NT) wl.layer_start[l] = 0;
         } else {
-            int64_t acc = sScan[tid] - run, acc2 = sScan2[tid] - run2;
+            int64_t acc = inc - run, acc2 = inc2 - run2;
             for (int y = y0; y < y1; ++y) {
                 const int l = y / B, b = y % B;
                 const RowUnits ru = row_units(sKept[b * L + l], T_max, ub, us);
@@ -145,7 +148,7 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
             if (tid == 0) wl.layer_start[L] = (int)total;
         }
         __syncthreads();
-        if (sBad) continue;
+        if (sBad) return;
         const int n_big = sTotals[0], n_live = sTotals[1];
         if (tid == 0) wl.layer_start[L + 1] = n_big;               // decode reverses the walk over the u_big units on odd steps
         for (int x = tid; x < BL * Hkv; x += NT) {
@@ -178,7 +181,11 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
                 wl.items[ws] = it;
             }
         }
-    }
+    };
+    build_list(dev.list[0]);
+    build_list(dev.list[1]);
+    if (dev.list[2].items != dev.list[0].items && dev.list[2].items != dev.list[1].items) build_list(dev.list[2]);   // else the gather shares a decode list
+    static_assert(kNumLists == 3, "one call per list");
 }
 
 __global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a, CacheDev dev) { layout_body<256>(a, dev); }
