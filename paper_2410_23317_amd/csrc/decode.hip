@@ -225,6 +225,12 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
     constexpr int KK = TK / 16;                 // slots per lane in the softmax step
     constexpr int DP = D + 2;
     constexpr bool SCATTER = (LPR == 16 && G <= 4);
+    // More than four query heads per KV head (bf16, d = 128): the logits of a tile come from the matrix cores,
+    // S = K Q^T with the query heads padded into the 32 columns of v_mfma_f32_32x32x16_bf16 (8 instructions per
+    // 32-slot tile instead of 7 x 32 packed dot products and their lane reductions; most columns are padding, but
+    // the matrix pipe is otherwise idle and the vector unit is what bounds these shapes).  A lane then fetches
+    // the K fragment it feeds to the instruction: row lane % 32 of the tile, 16 bytes at k-step 2 s + lane / 32.
+    constexpr bool MF = BF && !Q8 && D == 128 && G > 4;
     static_assert(G <= LPR, "one lane per head needed when parking logits");
     static_assert(NIT % 2 == 0, "P.V pairs consecutive loads");
 
@@ -325,11 +331,18 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         const T* vnew = reinterpret_cast<const T*>(A.v_new) + ((size_t)(lr * A.B + ib) * A.Hkv + hkv) * D;
         const float scale2 = (A.sm_scale ? A.sm_scale[il] : A.default_scale) * kLog2e;
 
-        uint4 qv[G];
+        uint4 qv[MF ? 1 : G];                       // vector path: the 16 bytes of each query row that match this lane's K bytes
+        uint4 qf[MF ? D / 16 : 1];                  // matrix path: B fragments, column lane % 32 = query head (zero beyond G)
+        const T* qrow = reinterpret_cast<const T*>(A.q) + ((size_t)(lr * A.B + ib) * A.Hq + (size_t)hkv * G) * D;
+        if constexpr (MF) {
+            const int n = lane & 31, half = lane >> 5;
 #pragma unroll
-        for (int h = 0; h < G; ++h)
-            qv[h] = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(A.q) +
-                                                    ((size_t)(lr * A.B + ib) * A.Hq + (size_t)hkv * G + h) * D + c * EP);
+            for (int ks = 0; ks < D / 16; ++ks)
+                qf[ks] = n < G ? *reinterpret_cast<const uint4*>(qrow + (size_t)n * D + ks * 16 + half * 8) : make_uint4(0, 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int h = 0; h < G; ++h) qv[h] = *reinterpret_cast<const uint4*>(qrow + (size_t)h * D + c * EP);
+        }
 
         // running max / sum live per 16-lane row: row r owns heads r*HR .. r*HR + HR - 1
         float m_run[HR], l_run[HR], acc[G][EP];
@@ -367,6 +380,14 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
                     const int key = t0 + i * KPI + sub;
                     ksc[i] = key < len ? Ksc[key] : 0.f;
                 }
+            } else if constexpr (MF) {
+                const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);   // wave-uniform
+                const int key = t0 + (lane & 31);
+                const T* src = (!full && key == new_slot) ? knew : Kbase + (int64_t)key * D;
+                const bool live = full || key < len;
+#pragma unroll
+                for (int ks = 0; ks < NIT; ++ks)
+                    kb[ks] = live ? *reinterpret_cast<const uint4*>(src + ks * 16 + (lane >> 5) * 8) : make_uint4(0, 0, 0, 0);
             } else {
                 const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);   // wave-uniform
 #pragma unroll
@@ -393,6 +414,21 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         auto tile_body = [&](auto fullc, int t0) {
             constexpr bool FULL = decltype(fullc)::value;
             // ---- logits of 32 slots -> LDS
+            if constexpr (MF) {
+                f32x16_t sacc = {0};
+#pragma unroll
+                for (int ks = 0; ks < NIT; ++ks)
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kb[ks]), __builtin_bit_cast(bf16x8_t, qf[ks]), sacc, 0, 0, 0);
+                // sacc[i] = <k_slot, q_head>: head = lane % 32, slot = 8 (i / 4) + 4 (lane / 32) + i % 4
+                const int n = lane & 31;
+                if (n < G) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int slot = 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                        sL[wave][slot][n] = (FULL || t0 + slot < len) ? sacc[i] * scale2 : -INFINITY;
+                    }
+                }
+            } else {
 #pragma unroll
             for (int i = 0; i < NIT; ++i) {
                 const int key = t0 + i * KPI + sub;
@@ -420,6 +456,7 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
                     }
                     if (c < G) sL[wave][i * KPI + sub][c] = live ? mine * rs : -INFINITY;
                 }
+            }
             }
             __builtin_amdgcn_wave_barrier();
             // ---- softmax bookkeeping: 16-lane row r handles heads r*HR.., lane column j slots j, j+16
