@@ -316,9 +316,11 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
     const int64_t mean_row = sum_k_max / s->L + T_max / 2;    // slots of an average row half-way through decode
     // ---- the library's own choices (measured on the ragged budgets of the 7B and 34B shapes)
-    // launches over all layers: 256-slot units, 512 once the mean row is long (per-unit overhead against balance)
+    // launches over all layers: 256-slot units, 512 once the mean row is long (per-unit overhead against balance),
+    // 1024 where a KV head serves more than four query heads (two blocks per CU and a longer merge: a unit's
+    // start and end cost more there)
     if (!o.unit_slots) {
-        o.unit_slots = mean_row >= 768 ? 512 : 256;
+        o.unit_slots = mean_row >= 768 ? (s->Hq / s->Hkv > 4 ? 1024 : 512) : 256;
         if (o.tail_unit_slots > o.unit_slots) o.unit_slots = o.tail_unit_slots;
     }
     if (!o.tail_unit_slots) o.tail_unit_slots = o.unit_slots;
@@ -443,6 +445,14 @@ static vlc_status cache_create_common(const char* who, const vlc_shape* shape, i
     c->kv_fp8 = plan.opt.kv_fp8 != 0;
     c->ragged = false;
     c->compacted = false;
+    {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+            (void)hipGetLastError();
+            cus = 256;
+        }
+        c->num_cus = cus;
+    }
     *out = c;
     return VLC_OK;
 }

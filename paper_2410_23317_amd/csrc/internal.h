@@ -81,6 +81,7 @@ struct vlc_cache {
     bool compacted;
     bool kv_fp8;                       // rows stored as E4M3 codes + per-row scale
     bool ragged;                       // the last compaction had per-request lengths (dev.lens is valid)
+    int32_t num_cus;                   // compute units of the device the cache was created on
     int32_t appended[vlc::kMaxLayers]; // decode appends enqueued so far, per layer (the device keeps the count the kernels use)
 };
 
