@@ -36,6 +36,16 @@
 #include "common.h"
 #include "internal.h"
 
+// Measurement builds only (the library then computes wrong results on purpose; the default, 0, is the product):
+// -DVLC_DECODE_ABLATE=<bits> takes phases out of the attention kernel so that their share of a launch can be
+// timed.  1: the tiles are loaded and waited for, but no arithmetic is done on them; 2: a block-unit ends after
+// its last tile (no merge of the waves, no partials, no output); 4: every block-unit is treated as a whole row
+// (the merge of the waves and the output store stay, the partials and the cross-block count go).  All accesses
+// stay in bounds in every combination.
+#ifndef VLC_DECODE_ABLATE
+#define VLC_DECODE_ABLATE 0
+#endif
+
 namespace vlc {
 namespace {
 
@@ -318,7 +328,11 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
             return true;
         }
         const int nbig = kept >> A.ub_shift;    // units of this row that hold slots now: the whole ones, and the small ones up to len
+#if VLC_DECODE_ABLATE & 4
+        const int nu = 1;
+#else
         const int nu = nbig + ((len - (nbig << A.ub_shift) + (1 << A.us_shift) - 1) >> A.us_shift);
+#endif
         const int cap = kept + A.T_max;
         const int new_slot = appending ? len - 1 : -1;
         const T* Kbase = reinterpret_cast<const T*>(A.dev.kv) + kbase;
@@ -435,6 +449,15 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         };
         auto tile_body = [&](auto fullc, int t0) {
             constexpr bool FULL = decltype(fullc)::value;
+#if VLC_DECODE_ABLATE & 1
+            if constexpr (!Q8) {                // every loaded word is used once, so the loads and their waits stay
+                uint32_t x = 0;
+#pragma unroll
+                for (int i = 0; i < NIT; ++i) x ^= kb[i].x ^ kb[i].y ^ kb[i].z ^ kb[i].w ^ vb[i].x ^ vb[i].y ^ vb[i].z ^ vb[i].w;
+                acc[0][0] += __uint_as_float(x & 0x3fffffu);
+                return;
+            }
+#endif
             // ---- logits of 32 slots -> LDS
             if constexpr (MF) {
                 f32x16_t sacc = {0};
@@ -592,6 +615,11 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
             if (c == 0) A.dev.idx[idx_base + new_slot] = A.m + appended;
         }
 
+#if VLC_DECODE_ABLATE & 2
+        if (acc[0][0] == 1.2345f) Elem<T>::store(outp, acc[0][0]);     // keeps the accumulators alive; practically never taken
+        if (mode && tid == 0) finish(ticket, il, n_layer);
+        return true;
+#endif
         // ---- sum the row groups of the wave, then merge the 4 waves through LDS
 #pragma unroll
         for (int off = LPR; off < 64; off <<= 1)
