@@ -318,7 +318,7 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     // ---- the library's own choices (measured on the ragged budgets of the 7B and 34B shapes)
     // launches over all layers: 256-slot units, 512 once the mean row is long (per-unit overhead against balance),
     // 1024 where a KV head serves more than four query heads (two blocks per CU and a longer merge: a unit's
-    // start and end cost more there)
+    // start and end cost more there; measured on the bf16 and the FP8 cache)
     if (!o.unit_slots) {
         o.unit_slots = mean_row >= 768 ? (s->Hq / s->Hkv > 4 ? 1024 : 512) : 256;
         if (o.tail_unit_slots > o.unit_slots) o.unit_slots = o.tail_unit_slots;

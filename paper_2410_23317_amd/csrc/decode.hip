@@ -20,8 +20,9 @@
 // partials in scratch; the unit that finishes last (device-scope counter) merges them.  The
 // partials and the counter are only ever touched with device-scope atomic accesses, which
 // are coherent across the XCDs' L2 caches by themselves, so no cache-wide release/acquire
-// fence is needed (those cost tens of microseconds here).  Matrix cores are not used: with
-// g <= 8 query rows per KV head the work is a stream, not a contraction.
+// fence is needed (those cost tens of microseconds here).  With g <= 8 query rows per KV head the
+// work is a stream, not a contraction; the matrix cores only take over step 2 when g > 4 (bf16,
+// d = 128), where the vector unit would otherwise be the bound.
 //
 // Nothing that changes from step to step is a launch parameter: the number of appends a layer has
 // received is read from the cache (dev.appended), and the launch that appends leaves count + 1 behind.
