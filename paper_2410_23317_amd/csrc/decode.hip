@@ -395,11 +395,21 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         };
         auto issue_k = [&](int t0) {
             if constexpr (Q8) {
+                if (t0 + TK <= len) {           // whole tile (wave-uniform): no per-row tests, one lane offset, constant displacements
+                    const uint32_t off = (uint32_t)(t0 + sub) * D + c * 8;
+                    const uint32_t so = (uint32_t)(t0 + sub) * (uint32_t)sizeof(float);
 #pragma unroll
-                for (int i = 0; i < NIT; ++i) {
-                    kb8[i] = load_row8(K8, t0, i);
-                    const int key = t0 + i * KPI + sub;
-                    ksc[i] = key < len ? Ksc[key] : 0.f;
+                    for (int i = 0; i < NIT; ++i) {
+                        kb8[i] = *reinterpret_cast<const uint2*>(K8 + off + (size_t)i * KPI * D);
+                        ksc[i] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(Ksc) + so + (size_t)i * KPI * sizeof(float));
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NIT; ++i) {
+                        kb8[i] = load_row8(K8, t0, i);
+                        const int key = t0 + i * KPI + sub;
+                        ksc[i] = key < len ? Ksc[key] : 0.f;
+                    }
                 }
             } else if constexpr (MF) {
                 const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);   // wave-uniform
@@ -424,12 +434,22 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         };
         auto issue_v = [&](int t0) {
             if constexpr (Q8) {
+                if (t0 + TK <= len) {
+                    const uint32_t off = (uint32_t)(t0 + sub) * D + c * 8;
+                    const uint32_t so = (uint32_t)(t0 + scol) * (uint32_t)sizeof(float);
 #pragma unroll
-                for (int i = 0; i < NIT; ++i) vb8[i] = load_row8(V8, t0, i);
+                    for (int i = 0; i < NIT; ++i) vb8[i] = *reinterpret_cast<const uint2*>(V8 + off + (size_t)i * KPI * D);
 #pragma unroll
-                for (int kk = 0; kk < KK; ++kk) {
-                    const int key = t0 + scol + 16 * kk;          // the slots this lane owns in the softmax step
-                    vsc[kk] = key < len ? Vsc[key] : 0.f;
+                    for (int kk = 0; kk < KK; ++kk)
+                        vsc[kk] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(Vsc) + so + (size_t)kk * 16 * sizeof(float));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < NIT; ++i) vb8[i] = load_row8(V8, t0, i);
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) {
+                        const int key = t0 + scol + 16 * kk;      // the slots this lane owns in the softmax step
+                        vsc[kk] = key < len ? Vsc[key] : 0.f;
+                    }
                 }
             } else {
                 const bool full = (t0 + TK <= len) && !(new_slot >= t0 && new_slot < t0 + TK);

@@ -146,6 +146,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     const int k_begin = split * a.keys_per_split;
     const int k_end = min(mb, k_begin + a.keys_per_split);
 
+    // the first K chunk is requested before anything else: the prologue below (Q' fragments, then the merge of
+    // sweep 1's partials with its barrier) runs while it is on its way
+    KStage<THREADS> st;
+    if (k_begin < k_end) st.load(kg, k_begin, mb);
     uint4 qf[RB][kKSteps];
     load_q_frags<WAVES, RB>(a, bl, hkv, wave, lane, tb, qf);
     // per accumulator slot: exponent offset (+inf for padded rows) and 1 / row sum
@@ -203,8 +207,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
         }
     }
 
-    KStage<THREADS> st;
-    if (k_begin < k_end) st.load(kg, k_begin, mb);
     for (int kc = k_begin; kc < k_end; kc += kChunk) {
         __syncthreads();
         st.store(sK);
