@@ -41,8 +41,9 @@
 // -DVLC_DECODE_ABLATE=<bits> takes phases out of the attention kernel so that their share of a launch can be
 // timed.  1: the tiles are loaded and waited for, but no arithmetic is done on them; 2: a block-unit ends after
 // its last tile (no merge of the waves, no partials, no output); 4: every block-unit is treated as a whole row
-// (the merge of the waves and the output store stay, the partials and the cross-block count go).  All accesses
-// stay in bounds in every combination.
+// (the merge of the waves and the output store stay, the partials and the cross-block count go); 8: the appended
+// row is not copied into the cache (its position is still recorded and the count advances).  All accesses stay in
+// bounds in every combination.
 #ifndef VLC_DECODE_ABLATE
 #define VLC_DECODE_ABLATE 0
 #endif
@@ -628,7 +629,7 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         }
 
         // The unit that holds the new slot also stores the new row into the cache.
-        if (!Q8 && appending && new_slot >= key0 && new_slot < key0 + ucap && wave == 0 && sub == 0) {
+        if (!(VLC_DECODE_ABLATE & 8) && !Q8 && appending && new_slot >= key0 && new_slot < key0 + ucap && wave == 0 && sub == 0) {
             T* kdst = const_cast<T*>(Kbase) + (int64_t)new_slot * D;
             T* vdst = const_cast<T*>(Vbase) + (int64_t)new_slot * D;
             *reinterpret_cast<uint4*>(kdst + c * EP) = *reinterpret_cast<const uint4*>(knew + c * EP);
