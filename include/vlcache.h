@@ -80,9 +80,10 @@ typedef struct {
     int32_t reserved;          /* 0 */
 } vlc_shape;
 
-/* vlc_shape.flags: take the plain-ALU scoring sweeps even where the matrix-core sweeps cover the shape
- * (bf16, d = 128).  Same results to the scoring tolerance; a cross-check for tests.  vlc_workspace_bytes
- * and the scoring calls read the flag from the same shape, so the size query and the call always agree. */
+/* vlc_shape.flags: take the plain-ALU scoring sweeps, and the generic window-attention kernel, even where the
+ * matrix-core kernels cover the shape (bf16, d = 128).  Same results to the stated tolerances; a cross-check
+ * for tests.  The workspace queries and the calls read the flag from the same shape, so a size query and the
+ * call it is for always agree. */
 #define VLC_SHAPE_SCORE_PLAIN_ALU 1
 
 const char* vlc_last_error_string(void);
@@ -158,13 +159,17 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
  *   out[b,l,h,i,:] = sum over valid j of A'_ij * v[b,l,h/g,j,:]     (A', validity as under vlc_score)
  *   row_max, row_sum = M_i, Z_i of the same softmax
  *
- * q_win   [B,L,Hq,tau,d]  in   bf16
- * k, v    [B,L,Hkv,m,d]   in   bf16
- * out     [B,L,Hq,tau,d]  out  bf16 (fp32 accumulation, probabilities rounded to bf16 for the product)
+ * q_win   [B,L,Hq,tau,d]  in   storage dtype
+ * k, v    [B,L,Hkv,m,d]   in   storage dtype
+ * out     [B,L,Hq,tau,d]  out  storage dtype (fp32 accumulation)
  * row_max, row_sum [B,L,Hq,tau] out fp32
- * workspace               scratch of at least vlc_window_attn_workspace_bytes(shape) bytes
- * Built for dtype VLC_BF16 and d = 128: both calls return VLC_ERR_UNIMPLEMENTED otherwise (the workspace
- * query then stores 0).  With shape->lens, rows >= tau_b of request b are left untouched.
+ * workspace               scratch of at least vlc_window_attn_workspace_bytes(shape) bytes; may be NULL when
+ *                         that is 0
+ * Two kernels: bf16 storage with d = 128 runs on the matrix cores (probabilities rounded to bf16 for the
+ * P.V product; key range split over blocks, partial results in the workspace); every other dtype / d, and
+ * that shape too when shape->flags has VLC_SHAPE_SCORE_PLAIN_ALU, runs a generic kernel (one wave per window
+ * row, fp32 probabilities, no workspace: the query stores 0), written for coverage rather than speed.
+ * With shape->lens, rows >= tau_b of request b are left untouched.
  */
 vlc_status vlc_window_attn_workspace_bytes(const vlc_shape* shape, size_t* bytes_out);
 vlc_status vlc_window_attn(const vlc_shape* shape, const void* q_win, const void* k, const void* v,

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libvlcache.so")
 
-SOURCES = ["api.hip", "score_simple.hip", "score_mfma.hip", "window_attn.hip", "allocate.hip", "topk_compact.hip", "decode.hip", "probe.hip"]
+SOURCES = ["api.hip", "score_simple.hip", "score_mfma.hip", "window_attn.hip", "window_attn_simple.hip", "allocate.hip", "topk_compact.hip", "decode.hip", "probe.hip"]
 
 # packed fp32 VALU ops are switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("VLC_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

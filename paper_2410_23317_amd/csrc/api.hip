@@ -205,13 +205,17 @@ vlc_status vlc_sparsity(const vlc_shape* shape, const void* q_win, const void* k
     return VLC_OK;
 }
 
+// The matrix-core attention kernel takes bf16 storage with d = 128; every other shape, and that one too when the
+// shape asks for the plain-ALU route, goes to the generic kernel, which needs no workspace.
+static bool window_attn_on_matrix_cores(const vlc_shape& s) {
+    return vlc::window_attn_supported(s) && !(s.flags & VLC_SHAPE_SCORE_PLAIN_ALU);
+}
+
 vlc_status vlc_window_attn_workspace_bytes(const vlc_shape* shape, size_t* bytes_out) {
     if (!bytes_out) return fail(VLC_ERR_INVALID_ARG, "vlc_window_attn_workspace_bytes: bytes_out is NULL");
     *bytes_out = 0;
     if (vlc_status st = check_shape(shape)) return st;
-    if (!vlc::window_attn_supported(*shape))
-        return fail(VLC_ERR_UNIMPLEMENTED, "vlc_window_attn: built for bf16 storage and d = 128 only");
-    *bytes_out = vlc::window_attn_workspace_bytes(*shape);
+    if (window_attn_on_matrix_cores(*shape)) *bytes_out = vlc::window_attn_workspace_bytes(*shape);
     return VLC_OK;
 }
 
@@ -219,17 +223,17 @@ vlc_status vlc_window_attn(const vlc_shape* shape, const void* q_win, const void
                            const float* sm_scale, void* out, float* row_max, float* row_sum,
                            void* workspace, size_t workspace_bytes, vlc_stream stream) {
     if (vlc_status st = check_shape(shape)) return st;
-    if (!vlc::window_attn_supported(*shape))
-        return fail(VLC_ERR_UNIMPLEMENTED, "vlc_window_attn: built for bf16 storage and d = 128 only");
-    if (!q_win || !k || !v || !out || !row_max || !row_sum || !workspace)
-        return fail(VLC_ERR_INVALID_ARG, "vlc_window_attn: q_win, k, v, out, row_max, row_sum and workspace must not be NULL");
-    const size_t need = vlc::window_attn_workspace_bytes(*shape);
+    if (!q_win || !k || !v || !out || !row_max || !row_sum)
+        return fail(VLC_ERR_INVALID_ARG, "vlc_window_attn: q_win, k, v, out, row_max and row_sum must not be NULL");
+    const bool mfma = window_attn_on_matrix_cores(*shape);
+    const size_t need = mfma ? vlc::window_attn_workspace_bytes(*shape) : 0;
+    if (need && !workspace) return fail(VLC_ERR_INVALID_ARG, "vlc_window_attn: workspace must not be NULL for this shape");
     if (workspace_bytes < need)
         return fail(VLC_ERR_CAPACITY, "vlc_window_attn: workspace of %zu bytes, %zu needed", workspace_bytes, need);
     vlc::WindowAttnArgs a;
     a.s = *shape; a.q_win = q_win; a.k = k; a.v = v; a.sm_scale = sm_scale; a.out = out;
     a.row_max = row_max; a.row_sum = row_sum; a.workspace = workspace; a.stream = (hipStream_t)stream;
-    const hipError_t e = vlc::launch_window_attn(a);
+    const hipError_t e = mfma ? vlc::launch_window_attn(a) : vlc::launch_window_attn_simple(a);
     if (e != hipSuccess) return hip_fail(e, "vlc_window_attn");
     return VLC_OK;
 }

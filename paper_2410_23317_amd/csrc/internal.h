@@ -127,6 +127,7 @@ struct WindowAttnArgs {
 bool window_attn_supported(const vlc_shape& s);
 size_t window_attn_workspace_bytes(const vlc_shape& s);
 hipError_t launch_window_attn(const WindowAttnArgs& a);
+hipError_t launch_window_attn_simple(const WindowAttnArgs& a);      // any dtype and d (window_attn_simple.hip); no workspace
 
 // ---- allocation ----
 hipError_t launch_allocate(const vlc_shape& s, const uint64_t* nnz, int64_t alpha_num, int64_t alpha_den,

@@ -55,8 +55,8 @@ class VLCachePath:
                     self.workspace)
 
     def window_attn(self, q_win, k, v, sm_scale, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        """Attention of the window rows that also fills row_max / row_sum (bf16, d = 128): with it the
-        scores come from score_from_stats and the row-statistics sweep of score() is not run."""
+        """Attention of the window rows that also fills row_max / row_sum: with it the scores come from
+        score_from_stats and the row-statistics sweep of score() is not run."""
         if out is None:
             out = torch.empty_like(q_win)
         if getattr(self, "win_workspace", None) is None:

@@ -70,16 +70,19 @@ def test_argument_validation_happens_before_any_launch(V):
 def test_window_attn_and_score_from_stats_validate_before_any_launch(V):
     f32 = V.make_shape(1, 2, 4, 2, 64, 512, 32, "f32")
     nbytes = C.c_size_t(7)
-    assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32), C.byref(nbytes)) == V.VLC_ERR_UNIMPLEMENTED
-    assert nbytes.value == 0 and "bf16" in V.vlc_last_error_string()
+    assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32), C.byref(nbytes)) == V.VLC_OK
+    assert nbytes.value == 0                                     # the generic kernel (fp32 storage, d = 64) needs no workspace
     assert V.lib.vlc_window_attn_workspace_bytes(C.byref(f32), None) == V.VLC_ERR_INVALID_ARG
-    assert V.lib.vlc_window_attn(C.byref(f32), 1, 1, 1, None, 1, 1, 1, 1, 1 << 30, None) == V.VLC_ERR_UNIMPLEMENTED
+    assert V.lib.vlc_window_attn(C.byref(f32), 1, 1, None, None, 1, 1, 1, None, 0, None) == V.VLC_ERR_INVALID_ARG   # v missing
+    plain = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16", flags=V.VLC_SHAPE_SCORE_PLAIN_ALU)
+    assert V.vlc_window_attn_workspace_bytes(plain) == 0         # the flag sends the matrix-core shape to the generic kernel too
     s = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16")
     sp = C.byref(s)
     need = V.vlc_window_attn_workspace_bytes(s)
     assert need >= 2 * 2 * 4 * 32 * 128 * 4                      # at least one split of fp32 partial outputs
     assert V.lib.vlc_window_attn(sp, 1, 1, None, None, 1, 1, 1, 1, need, None) == V.VLC_ERR_INVALID_ARG     # v missing
     assert V.lib.vlc_window_attn(sp, 1, 1, 1, None, 1, 1, 1, 1, need - 1, None) == V.VLC_ERR_CAPACITY
+    assert V.lib.vlc_window_attn(sp, 1, 1, 1, None, 1, 1, 1, None, need, None) == V.VLC_ERR_INVALID_ARG      # workspace missing
     big = V.make_shape(2, 32, 8, 8, 128, 3000, 32, "bf16")         # every KV group has a block of its own: no partials
     assert V.vlc_window_attn_workspace_bytes(big) == 256
     assert V.lib.vlc_score_from_stats(sp, 1, 1, None, 0.01, None, 1, 1, None, None) == V.VLC_ERR_INVALID_ARG

@@ -149,6 +149,14 @@ def test_cfg1_7b_shape_all_layers():
     run_and_check(cfg, cfg.alphas[0], 4)
 
 
+def test_cfg0_tiny_fp32_takes_the_fused_statistics_route():
+    """Config 0 (fp32 storage, d = 64): window attention with row statistics from the generic kernel, then the
+    column sweep from them, every request and layer against the oracle."""
+    from gpu_util import check_window_attn, upload
+    cfg = W.CONFIGS[0]
+    check_window_attn(cfg, upload(cfg), list(range(cfg.B)), list(range(cfg.L)))
+
+
 def test_cfg1_7b_shape_window_attention():
     from gpu_util import check_window_attn, upload
     cfg = W.CONFIGS[1]

@@ -156,8 +156,106 @@ def test_score_from_stats_takes_the_statistics_as_given_fp32_storage():
         psi, _ = O.score_from_stats(host[l]["q_win"], host[l]["k"], scales[l], Ms[l], Zs[l])
         assert_close(scores[0, l].cpu().numpy(), psi, what=f"l={l} scores", **SCORE_TOL)
         check_nnz(nnz[0, l].cpu().numpy(), host[l]["q_win"], host[l]["k"], scales[l], 0.01, f"l={l} nnz")
-    with pytest.raises(V.VlcError):
-        V.vlc_window_attn_workspace_bytes(shape)             # the attention kernel is built for bf16, d = 128
+    assert V.vlc_window_attn_workspace_bytes(shape) == 0     # this shape takes the generic attention kernel
+
+
+F32_OUT_TOL = dict(atol=1e-4, rtol=1e-4)     # fp32 storage: fp32 probabilities, fp32 accumulation
+
+
+@pytest.mark.parametrize("cid,dtype,d,B,L,Hq,Hkv,m,tau,plain", [
+    (440, "f32", 64, 2, 2, 4, 2, 300, 20, False),      # the tiny fp32 shape class (config 0)
+    (441, "f32", 128, 1, 2, 8, 2, 200, 33, False),     # fp32 storage, d = 128; a row count that is not a multiple of 4
+    (442, "bf16", 64, 1, 2, 6, 2, 257, 16, False),     # bf16 storage, d = 64: 2-byte elements per lane
+    (443, "bf16", 128, 1, 2, 8, 2, 500, 40, True),     # the matrix-core shape sent to the generic kernel by the flag
+    (444, "f32", 64, 1, 1, 2, 2, 64, 64, False),       # window = whole prompt: one tile, row 0 sees one key
+    (445, "f32", 64, 1, 1, 1, 1, 65, 1, False),        # one window row, a second tile with one key
+])
+def test_generic_window_attn_matches_the_oracle_and_feeds_the_column_sweep(cid, dtype, d, B, L, Hq, Hkv, m, tau, plain):
+    """The attention kernel for shapes outside the matrix-core path (fp32 storage, d = 64) and its statistics as
+    inputs of vlc_score_from_stats: outputs, M, Z, scores and counts against the oracle; for the flagged bf16 shape
+    also against the matrix-core kernel on the same inputs."""
+    import paper_2410_23317_amd as V
+    cfg = _cfg(cid, B, L, Hq, Hkv, m, tau, dtype=dtype, d=d)
+    dt = torch_dtype(cfg)
+    q_win = torch.empty((B, L, Hq, tau, d), dtype=dt, device="cuda")
+    k = torch.empty((B, L, Hkv, m, d), dtype=dt, device="cuda")
+    v = torch.empty_like(k)
+    host = {}
+    for b in range(B):
+        for l in range(L):
+            t = W.layer_inputs(cfg, b, l)
+            host[(b, l)] = t
+            q_win[b, l].copy_(torch.from_numpy(t["q_win"]).to(dt))
+            k[b, l].copy_(torch.from_numpy(t["k"]).to(dt))
+            v[b, l].copy_(torch.from_numpy(t["v"]).to(dt))
+    scales = W.sm_scale(cfg)
+    sm = torch.from_numpy(scales).cuda()
+    shape = V.make_shape(B, L, Hq, Hkv, d, m, tau, dtype, flags=V.VLC_SHAPE_SCORE_PLAIN_ALU if plain else 0)
+    assert V.vlc_window_attn_workspace_bytes(shape) == 0
+    out = torch.full((B, L, Hq, tau, d), 7.0, dtype=dt, device="cuda")
+    row_max = torch.full((B, L, Hq, tau), 123.0, dtype=torch.float32, device="cuda")
+    row_sum = torch.full((B, L, Hq, tau), 123.0, dtype=torch.float32, device="cuda")
+    V.vlc_window_attn(shape, q_win, k, v, sm, out, row_max, row_sum, None)
+    scores = torch.full((B, L, Hkv, m), float("nan"), dtype=torch.float32, device="cuda")
+    nnz = torch.full((B, L, Hq), 99, dtype=torch.int64, device="cuda")
+    V.vlc_score_from_stats(shape, q_win, k, sm, 0.01, row_max, row_sum, scores, nnz)
+    torch.cuda.synchronize()
+    tol = OUT_TOL if dtype == "bf16" else F32_OUT_TOL
+    for (b, l), t in host.items():
+        what = f"cid={cid} b={b} l={l}"
+        o_ref, M, Z = O.window_attention(t["q_win"], t["k"], t["v"], scales[l])
+        assert_close(out[b, l].float().cpu().numpy(), o_ref, what=what + " out", **tol)
+        assert_close(row_max[b, l].cpu().numpy(), M, atol=2e-5, rtol=2e-6, what=what + " row_max")
+        assert_close(row_sum[b, l].cpu().numpy(), Z, atol=0, rtol=5e-5, what=what + " row_sum")
+        psi, _ = O.score_from_stats(t["q_win"], t["k"], scales[l], M, Z)
+        assert_close(scores[b, l].cpu().numpy(), psi, what=what + " scores", **SCORE_TOL)
+        check_nnz(nnz[b, l].cpu().numpy(), t["q_win"], t["k"], scales[l], 0.01, what + " nnz")
+    if plain:
+        mshape = V.make_shape(B, L, Hq, Hkv, d, m, tau, dtype)
+        out2, M2, Z2, _, _ = _run(V, mshape, q_win, k, v, sm)
+        assert_close(out.float().cpu().numpy(), out2.float().cpu().numpy(), what="generic vs matrix-core out", **OUT_TOL)
+        assert_close(row_max.cpu().numpy(), M2.cpu().numpy(), atol=2e-5, rtol=2e-6, what="generic vs matrix-core row_max")
+        assert_close(row_sum.cpu().numpy(), Z2.cpu().numpy(), atol=0, rtol=5e-5, what="generic vs matrix-core row_sum")
+
+
+def test_generic_window_attn_ragged_batch_fp32():
+    """Per-request (m_b, tau_b) with NaN in all padding: the generic kernel reads nothing beyond a request's own rows
+    and leaves the window rows beyond tau_b untouched."""
+    import paper_2410_23317_amd as V
+    lens = [(300, 20), (77, 5), (64, 33)]
+    Hq, Hkv, L, d = 4, 2, 2, 64
+    cfgs = [_cfg(450 + i, 1, L, Hq, Hkv, m, tau, dtype="f32", d=d) for i, (m, tau) in enumerate(lens)]
+    B, m_max, tau_max = len(lens), 300, 33
+    q_win = torch.full((B, L, Hq, tau_max, d), float("nan"), dtype=torch.float32, device="cuda")
+    k = torch.full((B, L, Hkv, m_max, d), float("nan"), dtype=torch.float32, device="cuda")
+    v = torch.full((B, L, Hkv, m_max, d), float("nan"), dtype=torch.float32, device="cuda")
+    host = {}
+    for b, cfg in enumerate(cfgs):
+        for l in range(L):
+            t = W.layer_inputs(cfg, 0, l)
+            host[(b, l)] = t
+            q_win[b, l, :, : cfg.tau].copy_(torch.from_numpy(t["q_win"]))
+            k[b, l, :, : cfg.m].copy_(torch.from_numpy(t["k"]))
+            v[b, l, :, : cfg.m].copy_(torch.from_numpy(t["v"]))
+    scales = W.sm_scale(cfgs[0])
+    sm = torch.from_numpy(scales).cuda()
+    lens_t = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    shape = V.make_shape(B, L, Hq, Hkv, d, m_max, tau_max, "f32", lens=lens_t)
+    out = torch.full((B, L, Hq, tau_max, d), 7.0, dtype=torch.float32, device="cuda")
+    row_max = torch.full((B, L, Hq, tau_max), 123.0, dtype=torch.float32, device="cuda")
+    row_sum = torch.full((B, L, Hq, tau_max), 123.0, dtype=torch.float32, device="cuda")
+    V.vlc_window_attn(shape, q_win, k, v, sm, out, row_max, row_sum, None)
+    torch.cuda.synchronize()
+    for b, cfg in enumerate(cfgs):
+        assert torch.all(out[b, :, :, cfg.tau:] == 7.0), "window rows beyond the request's are left untouched"
+        assert torch.all(row_max[b, :, :, cfg.tau:] == 123.0)
+        for l in range(L):
+            t = host[(b, l)]
+            what = f"ragged fp32 b={b} l={l}"
+            o_ref, M, Z = O.window_attention(t["q_win"], t["k"], t["v"], scales[l])
+            assert_close(out[b, l, :, : cfg.tau].cpu().numpy(), o_ref, what=what + " out", **F32_OUT_TOL)
+            assert_close(row_max[b, l, :, : cfg.tau].cpu().numpy(), M, atol=2e-5, rtol=2e-6, what=what + " row_max")
+            assert_close(row_sum[b, l, :, : cfg.tau].cpu().numpy(), Z, atol=0, rtol=5e-5, what=what + " row_sum")
 
 
 def test_the_output_tolerance_notices_a_wrong_oracle():
