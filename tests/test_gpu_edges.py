@@ -456,6 +456,40 @@ def test_rows_that_grow_across_a_unit_boundary_during_decode(unit, merge, order)
         path.status()
 
 
+@pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
+def test_growth_across_a_1024_slot_unit_with_seven_heads_per_kv_head(fp8):
+    """The unit size the library picks when a KV head serves more than four query heads (1024 slots), on the
+    matrix-core logits path (g = 7) and on the FP8 cache: rows of 1022 and 2046 kept slots grow across the unit
+    boundary during 6 steps; launches over all layers and per layer (512-slot units there), every step against the
+    oracle."""
+    V = _V()
+    cfg = _small_cfg(cid=90, m=3300, n_visual=3200, L=2, B=2, Hq=14, Hkv=2)
+    kk = np.array([[1022, 2046], [33, 1022]])
+    T = 6
+    for per_layer in (False, True):
+        opts = dict(unit_slots=1024, layer_unit_slots=512, kv_fp8=int(fp8))
+        path, dev, caches, scales = _direct_cache(V, cfg, kk, T, opts)
+        assert path.cache.layout.unit_slots == 1024 and path.cache.layout.layer_unit_slots == 512
+        if fp8:                                                  # the oracle attends over what the FP8 cache holds
+            for key, (kc, vc) in caches.items():
+                caches[key] = ([O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(x)) for x in kc], [O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(x)) for x in vc])
+        out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=torch.bfloat16, device="cuda")
+        for step in range(T):
+            d_host = W.decode_step_inputs(cfg, step)
+            dd = {n: torch.from_numpy(x).to(torch.bfloat16).cuda() for n, x in d_host.items()}
+            if per_layer:
+                for l in range(cfg.L):
+                    path.decode(l, l + 1, dd["q"][l], dd["k_new"][l], dd["v_new"][l], dev["sm_scale"], out[l])
+            else:
+                path.decode(0, cfg.L, dd["q"], dd["k_new"], dd["v_new"], dev["sm_scale"], out)
+            torch.cuda.synchronize()
+            if fp8:
+                d_host = dict(d_host, k_new=O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(d_host["k_new"])),
+                              v_new=O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(d_host["v_new"])))
+            _oracle_step(cfg, caches, scales, d_host, out.float().cpu().numpy(), step, f"unit=1024 g=7 fp8={fp8} per_layer={per_layer}")
+        path.status()
+
+
 @pytest.mark.parametrize("per_layer", [False, True], ids=["all-layers", "per-layer"])
 @pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
 def test_one_decode_step_replays_from_a_hip_graph(per_layer, fp8):
