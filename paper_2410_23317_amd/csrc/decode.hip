@@ -96,6 +96,16 @@ __device__ __forceinline__ float load_agent(const float* p) {
 __device__ __forceinline__ void store_agent(int32_t* p, int32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// two neighbouring floats (8-byte aligned) as one device-scope store
+__device__ __forceinline__ void store_agent2(float* p, float a, float b) {
+    const unsigned long long v = ((unsigned long long)__float_as_uint(b) << 32) | __float_as_uint(a);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// two neighbouring output elements as one store
+__device__ __forceinline__ void store_pair(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+__device__ __forceinline__ void store_pair(bf16_t* p, float a, float b) {
+    *reinterpret_cast<uint32_t*>(p) = (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+}
 __device__ __forceinline__ int32_t add_agent(int32_t* p, int32_t v) {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -248,7 +258,8 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
 
     __shared__ __align__(16) float sL[NW][TK][GP];        // logits, then fp32 probabilities (fp32 path)
     __shared__ __align__(16) uint32_t sPk[NW][TK / 2][GP]; // bf16 probability pairs of loads (2i, 2i+1)
-    __shared__ float sMerge[NW][G][DP];
+    constexpr int DL = D + 4;                   // LDS row of the wave merge: D outputs, max, sum; a multiple of 16 bytes
+    __shared__ __align__(16) float sMerge[NW][G][DL];
     __shared__ int sLast;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -643,50 +654,77 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         return true;
 #endif
         // ---- sum the row groups of the wave, then merge the 4 waves through LDS
-#pragma unroll
-        for (int off = LPR; off < 64; off <<= 1)
+        if constexpr (LPR == 16) {
+            // Four row groups = the four 16-lane rows of the wave.  Reduce-scatter with the lane-swap instructions
+            // (v_permlane16_swap, v_permlane32_swap: vector-unit moves, no trip through the LDS queue): of four
+            // accumulators x0..x3, row r ends up with the total of x_r, so four registers become one and every
+            // lane has something to write.  swap16(a, b) = ([a.r0, b.r0, a.r2, b.r2], [a.r1, b.r1, a.r3, b.r3]),
+            // swap32(a, b) = ([a.lo, b.lo], [a.hi, b.hi]).
+            auto pair_sum16 = [](float a, float b) {
+                const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+                return __uint_as_float(r[0]) + __uint_as_float(r[1]);       // [a.r0 + a.r1, b.r0 + b.r1, a.r2 + a.r3, b.r2 + b.r3]
+            };
+            auto pair_sum32 = [](float a, float b) {
+                const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+                return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+            };
 #pragma unroll
             for (int h = 0; h < G; ++h)
 #pragma unroll
-                for (int e = 0; e < EP; ++e) acc[h][e] += __shfl_xor(acc[h][e], off, 64);
-        if (sub == 0) {
+                for (int e = 0; e < EP; e += 4) {
+                    const float tot = pair_sum32(pair_sum16(acc[h][e], acc[h][e + 1]), pair_sum16(acc[h][e + 2], acc[h][e + 3]));
+                    sMerge[wave][h][c * EP + e + sub] = tot;                  // row `sub` holds the total of element e + sub
+                }
+        } else {
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
+            for (int off = LPR; off < 64; off <<= 1)
 #pragma unroll
-                for (int e = 0; e < EP; ++e) sMerge[wave][h][c * EP + e] = acc[h][e];
+                for (int h = 0; h < G; ++h)
+#pragma unroll
+                    for (int e = 0; e < EP; ++e) acc[h][e] += __shfl_xor(acc[h][e], off, 64);
+            if (sub == 0) {
+#pragma unroll
+                for (int h = 0; h < G; ++h)
+#pragma unroll
+                    for (int e = 0; e < EP; e += 4)
+                        *reinterpret_cast<float4*>(&sMerge[wave][h][c * EP + e]) = make_float4(acc[h][e], acc[h][e + 1], acc[h][e + 2], acc[h][e + 3]);
             }
         }
         if (scol == 0) {
 #pragma unroll
             for (int hh = 0; hh < HR; ++hh)
-                if (srow * HR + hh < G) {
-                    sMerge[wave][srow * HR + hh][D] = m_run[hh];
-                    sMerge[wave][srow * HR + hh][D + 1] = l_run[hh];
-                }
+                if (srow * HR + hh < G) *reinterpret_cast<float2*>(&sMerge[wave][srow * HR + hh][D]) = make_float2(m_run[hh], l_run[hh]);
         }
         __syncthreads();
+        // every thread merges two neighbouring output elements of one head: one weight per wave, one store
         float* part = A.dev.partials + (size_t)canon * G * DP;      // partials sit in the layer-major order
-        for (int x = tid; x < G * D; x += THREADS) {
-            const int h = x / D, e = x % D;
+        for (int x = tid; x < G * D / 2; x += THREADS) {
+            const int h = x / (D / 2), e = (x % (D / 2)) * 2;
+            float2 ml[NW];
             float mt = -INFINITY;
 #pragma unroll
-            for (int wv = 0; wv < NW; ++wv) mt = fmaxf(mt, sMerge[wv][h][D]);
-            float o = 0.f, lt = 0.f;
+            for (int wv = 0; wv < NW; ++wv) {
+                ml[wv] = *reinterpret_cast<const float2*>(&sMerge[wv][h][D]);
+                mt = fmaxf(mt, ml[wv].x);
+            }
+            float o0 = 0.f, o1 = 0.f, lt = 0.f;
 #pragma unroll
             for (int wv = 0; wv < NW; ++wv) {
-                const float mw = sMerge[wv][h][D];
-                const float wgt = (mw > -INFINITY) ? exp2_fast(mw - mt) : 0.f;
-                o = fmaf(sMerge[wv][h][e], wgt, o);
-                lt = fmaf(sMerge[wv][h][D + 1], wgt, lt);
+                const float wgt = (ml[wv].x > -INFINITY) ? exp2_fast(ml[wv].x - mt) : 0.f;
+                const float2 ov = *reinterpret_cast<const float2*>(&sMerge[wv][h][e]);
+                o0 = fmaf(ov.x, wgt, o0);
+                o1 = fmaf(ov.y, wgt, o1);
+                lt = fmaf(ml[wv].y, wgt, lt);
             }
             if (nu == 1) {
-                Elem<T>::store(outp + x, o / lt);
+                const float inv = __builtin_amdgcn_rcpf(lt);        // within an ulp of the quotient: far inside the output's rounding
+                store_pair(outp + h * D + e, o0 * inv, o1 * inv);
             } else if (A.merge_mode == 1) {
-                store_agent(part + h * DP + e, o);
-                if (e == 0) { store_agent(part + h * DP + D, mt); store_agent(part + h * DP + D + 1, lt); }
+                store_agent2(part + h * DP + e, o0, o1);
+                if (e == 0) store_agent2(part + h * DP + D, mt, lt);
             } else {
-                part[h * DP + e] = o;
-                if (e == 0) { part[h * DP + D] = mt; part[h * DP + D + 1] = lt; }
+                *reinterpret_cast<float2*>(part + h * DP + e) = make_float2(o0, o1);
+                if (e == 0) *reinterpret_cast<float2*>(part + h * DP + D) = make_float2(mt, lt);
             }
         }
         if (nu > 1 && A.merge_mode == 1) {
