@@ -246,7 +246,11 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
                     }
                 }
             }
-            col += __shfl_xor(col, 32, 64);                     // the lane halves hold different rows of the same key
+            {   // the lane halves hold different rows of the same key: lane l + lane l ^ 32, with the lane-swap
+                // instruction rather than a shuffle through the LDS queue
+                const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(col), __float_as_uint(col), false, false);
+                col = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+            }
             if (lane < 32) sCol[wave][t * 32 + lane] = col;
         }
         __syncthreads();
