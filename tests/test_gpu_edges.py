@@ -457,6 +457,38 @@ def test_rows_that_grow_across_a_unit_boundary_during_decode(unit, merge, order)
 
 
 @pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
+def test_launches_over_layer_ranges_that_are_neither_one_layer_nor_all(fp8):
+    """A decode step issued as launches over parts of the layer stack: [0,2) + [2,4) on even steps, [0,1) + [1,4) on
+    odd ones.  A launch then starts inside the layer-ordered work list and counts its layers' units on two levels;
+    every layer still receives one append per step.  Every step against the oracle, with rows that cross a unit
+    boundary on the way."""
+    V = _V()
+    cfg = _small_cfg(cid=91, m=1500, n_visual=1400, L=4, B=2, Hq=8, Hkv=2)
+    kk = np.array([[126, 300, 17, 254], [510, 1, 127, 700]])
+    T = 6
+    path, dev, caches, scales = _direct_cache(V, cfg, kk, T, dict(kv_fp8=int(fp8)))
+    if fp8:
+        for key, (kc, vc) in caches.items():
+            caches[key] = ([O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(x)) for x in kc],
+                           [O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(x)) for x in vc])
+    out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=torch.bfloat16, device="cuda")
+    for step in range(T):
+        d_host = W.decode_step_inputs(cfg, step)
+        dd = {n: torch.from_numpy(x).to(torch.bfloat16).cuda() for n, x in d_host.items()}
+        for a, b in (((0, 2), (2, 4)) if step % 2 == 0 else ((0, 1), (1, 4))):
+            path.decode(a, b, dd["q"][a:b], dd["k_new"][a:b], dd["v_new"][a:b], dev["sm_scale"], out[a:b])
+        torch.cuda.synchronize()
+        if fp8:
+            d_host = dict(d_host, k_new=O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(d_host["k_new"])),
+                          v_new=O.dequantize_e4m3_rows(*O.quantize_e4m3_rows(d_host["v_new"])))
+        _oracle_step(cfg, caches, scales, d_host, out.float().cpu().numpy(), step, f"layer ranges fp8={fp8}")
+    path.status()
+    lay = path.cache.layout
+    appended = path.cache.arena[lay.appended_off: lay.appended_off + 4 * cfg.L].view(torch.int32).cpu()
+    assert appended.tolist() == [T] * cfg.L, "every layer counted its appends on the device"
+
+
+@pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
 def test_growth_across_a_1024_slot_unit_with_seven_heads_per_kv_head(fp8):
     """The unit size the library picks when a KV head serves more than four query heads (1024 slots), on the
     matrix-core logits path (g = 7) and on the FP8 cache: rows of 1022 and 2046 kept slots grow across the unit
