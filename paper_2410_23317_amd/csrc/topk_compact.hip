@@ -35,9 +35,12 @@ __device__ __forceinline__ RowUnits row_units(int kk, int T_max, int ub, int us)
     return RowUnits{big, (rem + us - 1) / us, big + (rem + T_max + us - 1) / us};
 }
 
-// Runs in one block of NT threads (every thread of the block must enter).
+// Runs in TWO blocks of NT threads (every thread of a block must enter): the lists are independent of each other
+// once budgets and slab offsets are known, and those are cheap, so both blocks derive them and part 0 writes them
+// out, zeroes the counters and builds the layer-ordered list, while part 1 builds the list of the all-layer launches
+// (and the gather's, when that is a list of its own).  Errors are reported by part 0.
 template <int NT>
-__device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
+__device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
     const int32_t* __restrict__ k = a.k;
     const int32_t* __restrict__ lens = a.lens;
     const int B = a.B, L = a.L, Hkv = a.Hkv, m = a.m, tau = a.tau, d = a.d, T_max = a.T_max;
@@ -51,36 +54,41 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
     __shared__ int sBad;
     const int tid = threadIdx.x;
     const int BL = B * L;
-    if (tid < 4) dev.status[tid] = 0;
+    const bool first = part == 0;               // the part that owns everything but the lists of part 1
+    if (first && tid < 4) dev.status[tid] = 0;
     __syncthreads();
     // per-request lengths: checked here (the only place with an error channel), kept in the cache
-    for (int b = tid; b < B; b += NT) {
-        int mb = m, tb = tau;
-        if (lens) {
-            mb = lens[2 * b]; tb = lens[2 * b + 1];
-            if (mb < 1 || mb > m || tb < 1 || tb > tau || tb > mb) set_sticky(dev.status, VLC_ERR_INVALID_ARG, b, -2, mb);
+    if (first) {
+        for (int b = tid; b < B; b += NT) {
+            int mb = m, tb = tau;
+            if (lens) {
+                mb = lens[2 * b]; tb = lens[2 * b + 1];
+                if (mb < 1 || mb > m || tb < 1 || tb > tau || tb > mb) set_sticky(dev.status, VLC_ERR_INVALID_ARG, b, -2, mb);
+            }
+            const ReqLen rl = request_len(lens, b, m, tau);
+            dev.lens[2 * b] = rl.m; dev.lens[2 * b + 1] = rl.tau;
         }
-        const ReqLen rl = request_len(lens, b, m, tau);
-        dev.lens[2 * b] = rl.m; dev.lens[2 * b + 1] = rl.tau;
     }
     for (int x = tid; x < BL; x += NT) {
         int kk = k[x];
         if (kk < 1 || kk > request_len(lens, x / L, m, tau).m) {
-            set_sticky(dev.status, VLC_ERR_INVALID_ARG, x / L, x % L, kk);
+            if (first) set_sticky(dev.status, VLC_ERR_INVALID_ARG, x / L, x % L, kk);
             kk = 0;
         }
         sKept[x] = kk;
     }
-    for (int x = tid; x < BL * Hkv; x += NT) dev.counters[x] = 0;
-    for (int x = tid; x < L; x += NT) dev.appended[x] = 0;          // decode starts at step 0
-    for (int x = tid; x <= L; x += NT) dev.readers[x * kReaderStride] = 0;
+    if (first) {
+        for (int x = tid; x < BL * Hkv; x += NT) dev.counters[x] = 0;
+        for (int x = tid; x < L; x += NT) dev.appended[x] = 0;          // decode starts at step 0
+        for (int x = tid; x <= L; x += NT) dev.readers[x * kReaderStride] = 0;
+    }
     __syncthreads();
     // slab offsets, one thread per request; a request whose budgets do not fit keeps nothing
     for (int b = tid; b < B; b += NT) {
         int64_t acc = 0;
         for (int l = 0; l < L; ++l) acc += sKept[b * L + l] + T_max;
         const bool over = acc > slots_per_request;
-        if (over) set_sticky(dev.status, VLC_ERR_CAPACITY, b, -1, (int)min(acc, (int64_t)INT32_MAX));
+        if (over && first) set_sticky(dev.status, VLC_ERR_CAPACITY, b, -1, (int)min(acc, (int64_t)INT32_MAX));
         acc = 0;
         for (int l = 0; l < L; ++l) {
             if (over) sKept[b * L + l] = 0;
@@ -89,9 +97,11 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
         }
     }
     __syncthreads();
-    for (int x = tid; x < BL; x += NT) {
-        dev.kept[x] = sKept[x];
-        dev.slot_off[x] = sSlot[x];
+    if (first) {
+        for (int x = tid; x < BL; x += NT) {
+            dev.kept[x] = sKept[x];
+            dev.slot_off[x] = sSlot[x];
+        }
     }
     // The work lists.  Units per row, exclusive prefix over (layer, request) in that order, for all units
     // and separately for the u_big units and the live small ones (the size-class order).  Each thread sums
@@ -182,13 +192,16 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev) {
             }
         }
     };
-    build_list(dev.list[0]);
-    build_list(dev.list[1]);
-    if (dev.list[2].items != dev.list[0].items && dev.list[2].items != dev.list[1].items) build_list(dev.list[2]);   // else the gather shares a decode list
+    if (first) {
+        build_list(dev.list[0]);
+    } else {
+        build_list(dev.list[1]);
+        if (dev.list[2].items != dev.list[0].items && dev.list[2].items != dev.list[1].items) build_list(dev.list[2]);   // else the gather shares a decode list
+    }
     static_assert(kNumLists == 3, "one call per list");
 }
 
-__global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a, CacheDev dev) { layout_body<256>(a, dev); }
+__global__ __launch_bounds__(256) void layout_kernel(LayoutArgs a, CacheDev dev) { layout_body<256>(a, dev, (int)blockIdx.x); }   // two blocks
 
 // Order-preserving map float -> uint32 (larger float, larger key).
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -252,12 +265,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
     __shared__ uint32_t sel_bin, sel_above;
     __shared__ uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
     if constexpr (FOLD) {
-        if (blockIdx.x == 0) {                       // first, so that it starts with the first rows
-            layout_body<kSelThreads>(la, dev);
+        if (blockIdx.x < 2) {                        // first, so that they start with the first rows
+            layout_body<kSelThreads>(la, dev, (int)blockIdx.x);
             return;
         }
     }
-    const int row = FOLD ? (int)blockIdx.x - 1 : (int)blockIdx.x;
+    const int row = FOLD ? (int)blockIdx.x - 2 : (int)blockIdx.x;
     const int hkv = row % Hkv, bl = row / Hkv;
     int kk, mb;
     int64_t slot_off;
@@ -553,9 +566,9 @@ hipError_t launch_topk_compact(const vlc_cache& c, const int32_t* lens, const fl
     const int per_lane = (((s.m + kSelWaves - 1) / kSelWaves + 63) / 64);
     // the layout as one more block of the selection (short rows only), or as a kernel of its own
     const bool fold = c.opt.select_fold == 2 && per_lane <= 8;
-    if (!fold) layout_kernel<<<1, 256, 0, st>>>(la, c.dev);
+    if (!fold) layout_kernel<<<2, 256, 0, st>>>(la, c.dev);
 #define VLC_SELECT(NK) select_kernel<NK, false, false><<<rows, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la)
-    if (fold) select_kernel<8, false, true><<<rows + 1, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la);
+    if (fold) select_kernel<8, false, true><<<rows + 2, kSelThreads, 0, st>>>(scores, c.dev, s.L, s.Hkv, s.m, lens != nullptr, c.T_max, n_recent, recent_num, recent_den, idx_out, nullptr, nullptr, la);
     else if (per_lane <= 8) VLC_SELECT(8);
     else if (per_lane <= 24) VLC_SELECT(24);
     else if (per_lane <= 64) VLC_SELECT(64);
