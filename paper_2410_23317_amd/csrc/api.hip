@@ -319,12 +319,28 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     const size_t BL = (size_t)s->B * s->L;
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
     const int64_t mean_row = sum_k_max / s->L + T_max / 2;    // slots of an average row half-way through decode
-    // ---- the library's own choices (measured on the ragged budgets of the 7B and 34B shapes)
-    // launches over all layers: 256-slot units, 512 once the mean row is long (per-unit overhead against balance),
-    // 1024 where a KV head serves more than four query heads (two blocks per CU and a longer merge: a unit's
-    // start and end cost more there; measured on the bf16 and the FP8 cache)
+    // ---- the library's own choices
+    // Launches over all layers (measured on the ragged budgets of the 7B and 34B shapes at batch 1 to 16, on an
+    // MI355X: 256 CUs, three blocks of this kernel per CU, two when a KV head serves more than four query heads).
+    // The walk is by size class with the partly filled units longest first, so balance comes from the order; what
+    // the unit size trades is the cost of a unit's start, merge and cross-block chain against having enough units.
+    //   rows >= 4 x the resident blocks: 2048-slot units (most rows are one unit: no partials at all);
+    //   rows >= 1.3 x: the power of two above the mean row, so that an average row is one unit;
+    //   fewer rows: 512-slot units for long rows, 256 for short ones, so that the chip still fills.
+    // The longest-first order exists for up to kLayoutSortMax (request, layer) entries; beyond, the last rule.
     if (!o.unit_slots) {
-        o.unit_slots = mean_row >= 768 ? (s->Hq / s->Hkv > 4 ? 1024 : 512) : 256;
+        const int64_t rows = (int64_t)BL * s->Hkv;
+        const int g = s->Hq / s->Hkv;
+        const int64_t resident = 256 * ((g <= 4 && (s->dtype != VLC_F32 || s->d == 64)) ? 3 : 2);
+        int u = mean_row >= 768 ? 512 : 256;
+        if (BL <= (size_t)vlc::kLayoutSortMax) {
+            if (rows >= 4 * resident) u = 2048;
+            else if (rows * 10 >= resident * 13) {
+                u = 256;
+                while (u < mean_row && u < 2048) u <<= 1;
+            }
+        }
+        o.unit_slots = u;
         if (o.tail_unit_slots > o.unit_slots) o.unit_slots = o.tail_unit_slots;
     }
     if (!o.tail_unit_slots) o.tail_unit_slots = o.unit_slots;

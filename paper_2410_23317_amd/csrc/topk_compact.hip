@@ -49,9 +49,10 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
     __shared__ int32_t sFirst[kLayoutMaxBL];        // first unit of (b, l), kv head 0, in canon order
     __shared__ int64_t sSlot[kLayoutMaxBL];
     __shared__ int64_t sScan[NT], sScan2[NT];
-    __shared__ int32_t sBigFirst[kLayoutMaxBL], sLiveFirst[kLayoutMaxBL];
+    __shared__ int32_t sBigFirst[kLayoutMaxBL], sLiveFirst[kLayoutMaxBL], sResFirst[kLayoutMaxBL];
     __shared__ int sTotals[2];
     __shared__ int sBad;
+    __shared__ int16_t sPerm[kLayoutSortMax];      // (request, layer) entries in the order of the size-class walk's second class
     const int tid = threadIdx.x;
     const int BL = B * L;
     const bool first = part == 0;               // the part that owns everything but the lists of part 1
@@ -152,6 +153,7 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
                 sFirst[b * L + l] = (int)acc;
                 sBigFirst[b * L + l] = (int)(acc2 >> 32);
                 sLiveFirst[b * L + l] = (int)(acc2 & 0xffffffff);
+                sResFirst[b * L + l] = (int)acc - (int)(acc2 >> 32) - (int)(acc2 & 0xffffffff);    // reserve units listed before this entry's
                 acc += (int64_t)ru.total * Hkv;
                 acc2 += ((int64_t)ru.big * Hkv << 32) | (int64_t)(ru.live * Hkv);
             }
@@ -159,6 +161,47 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
         }
         __syncthreads();
         if (sBad) return;
+        // Size-class order, second class (the units that are partly filled): longest first, so that the blocks
+        // dispatched last, which decide when the launch ends, are the shortest.  All rows of a (request, layer) entry
+        // have the same fill, so the entries are ranked (by the slots their rows hold beyond whole u_big units,
+        // descending, ties in list order: a count over all entries, cheap while there are few) and the class's
+        // positions are the prefix sums in that order.  With more entries the class keeps the list order.
+        if (wl.by_size && BL <= kLayoutSortMax) {
+            for (int y = tid; y < BL; y += NT) {
+                const int kk = sKept[(y % B) * L + y / B], key = kk - (kk / ub) * ub;
+                int rank = 0;
+                for (int z = 0; z < BL; ++z) {
+                    const int kz = sKept[(z % B) * L + z / B], keyz = kz - (kz / ub) * ub;
+                    rank += (keyz > key || (keyz == key && z < y)) ? 1 : 0;
+                }
+                sPerm[rank] = (int16_t)y;
+            }
+            __syncthreads();
+            const int per2 = (BL + NT - 1) / NT;
+            const int r0 = tid * per2, r1 = min(BL, r0 + per2);
+            int runl = 0;
+            for (int r = r0; r < r1; ++r) {
+                const int y = sPerm[r];
+                runl += row_units(sKept[(y % B) * L + y / B], T_max, ub, us).live * Hkv;
+            }
+            int incl = runl;
+            for (int o = 1; o < 64; o <<= 1) {
+                const int v = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += v;
+            }
+            if (lane == 63) sScan[wv] = incl;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < NT / 64; ++w)
+                if (w < wv) incl += (int)sScan[w];
+            int accl = incl - runl;
+            for (int r = r0; r < r1; ++r) {
+                const int y = sPerm[r], bl = (y % B) * L + y / B;
+                sLiveFirst[bl] = accl;
+                accl += row_units(sKept[bl], T_max, ub, us).live * Hkv;
+            }
+            __syncthreads();
+        }
         const int n_big = sTotals[0], n_live = sTotals[1];
         if (tid == 0) wl.layer_start[L + 1] = n_big;               // decode reverses the walk over the u_big units on odd steps
         for (int x = tid; x < BL * Hkv; x += NT) {
@@ -174,8 +217,8 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
             it.kbase = ((so * 2 * Hkv) + (int64_t)h * cap) * d;
             it.idx_base = so * Hkv + (int64_t)h * cap;
             const int w0 = sFirst[bl] + h * ru.total;
-            // units of the third class that precede this row's in the list: all units before it minus big and live
-            const int res0 = n_big + n_live + (sFirst[bl] - sBigFirst[bl] - sLiveFirst[bl]) + h * nres;
+            // units of the third class that precede this row's in the list (all units before it minus big and live)
+            const int res0 = n_big + n_live + sResFirst[bl] + h * nres;
             wl.row_first[x] = w0;
             for (int u = 0; u < ru.total; ++u) {
                 it.unit = u;

@@ -135,7 +135,7 @@ def test_cache_options_are_validated_and_reported(V):
         return (lay.unit_slots, lay.tail_unit_slots, lay.layer_unit_slots)
 
     default = create()
-    assert default[0] in (256, 512, 1024) and default[1] <= default[0] and default[2] in (128, 256, 512)
+    assert default[0] in (256, 512, 1024, 2048) and default[1] <= default[0] and default[2] in (128, 256, 512)
     assert V.vlc_cache_bytes(s, 100, sum_k) == V.vlc_cache_bytes_opt(s, 100, sum_k, None)     # NULL options = the defaults
     assert create(unit_slots=1024, tail_unit_slots=128, layer_unit_slots=256) == (1024, 128, 256)
     assert create(unit_slots=128) == (128, 128, default[2])

@@ -456,6 +456,28 @@ def test_rows_that_grow_across_a_unit_boundary_during_decode(unit, merge, order)
         path.status()
 
 
+@pytest.mark.parametrize("B,L", [(6, 5), (40, 13)], ids=["30-entries-sorted", "520-entries-unsorted"])
+def test_size_class_walk_with_budgets_of_every_length(B, L):
+    """The size-class work list puts the partly filled units longest first while the (request, layer) entries fit
+    its sort (512), and in request-layer order beyond.  Budgets from 1 slot to several units, many of them equal
+    (ties in the sort), rows that end exactly on a unit boundary and rows that grow over one during the steps:
+    every step against the oracle, launches over all layers."""
+    V = _V()
+    cfg = _small_cfg(cid=92, m=800, n_visual=760, L=L, B=B, Hq=4, Hkv=2, d=64, tau=16)    # alpha 1/2: 400 slots a layer
+    rng = np.random.default_rng(92 + B)
+    kk = rng.choice(np.array([1, 2, 63, 126, 127, 128, 129, 200, 254, 256, 257, 300, 383, 384, 400]), size=(B, L))
+    T = 4
+    path, dev, caches, scales = _direct_cache(V, cfg, kk, T, dict(unit_slots=128, decode_order=2))
+    out = torch.empty((cfg.L, cfg.B, cfg.Hq, cfg.d), dtype=torch.bfloat16, device="cuda")
+    for step in range(T):
+        d_host = W.decode_step_inputs(cfg, step)
+        dd = {n: torch.from_numpy(x).to(torch.bfloat16).cuda() for n, x in d_host.items()}
+        path.decode(0, cfg.L, dd["q"], dd["k_new"], dd["v_new"], dev["sm_scale"], out)
+        torch.cuda.synchronize()
+        _oracle_step(cfg, caches, scales, d_host, out.float().cpu().numpy(), step, f"B={B} L={L}")
+    path.status()
+
+
 @pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
 def test_launches_over_layer_ranges_that_are_neither_one_layer_nor_all(fp8):
     """A decode step issued as launches over parts of the layer stack: [0,2) + [2,4) on even steps, [0,1) + [1,4) on
