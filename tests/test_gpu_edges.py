@@ -423,7 +423,7 @@ def _oracle_step(cfg, caches, scales, d_host, got, step, what):
         assert_close(got[l, b], want, what=f"{what} step {step} b={b} l={l}", **out_tol(cfg))
 
 
-@pytest.mark.parametrize("unit", [128, 256, 512])
+@pytest.mark.parametrize("unit", [128, 256, 512, 2048])
 @pytest.mark.parametrize("merge", [1, 2])
 @pytest.mark.parametrize("order", [1, 2])
 def test_rows_that_grow_across_a_unit_boundary_during_decode(unit, merge, order):
@@ -432,7 +432,8 @@ def test_rows_that_grow_across_a_unit_boundary_during_decode(unit, merge, order)
     result from a direct store to a merge of partials.  Every step against the oracle, launches over all layers
     and per layer, both merge forms, both orders of the work list."""
     V = _V()
-    cfg = _small_cfg(cid=88, m=1200, n_visual=1100, L=3, B=2, Hq=8, Hkv=2)
+    m = 1200 if unit <= 512 else 4400           # the arena holds m / 2 slots per layer (alpha = 1/2)
+    cfg = _small_cfg(cid=88, m=m, n_visual=m - 100, L=3, B=2, Hq=8, Hkv=2)
     kk = np.array([[unit - 2, 2 * unit - 2, 40], [unit - 2, 7, 2 * unit - 2]])
     T = 6
     for per_layer in (False, True):
