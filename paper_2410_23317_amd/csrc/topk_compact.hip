@@ -284,8 +284,8 @@ __device__ __forceinline__ void for_keys(const uint32_t (&key)[NK > 0 ? NK : 1],
 // One block per (request, layer, KV head) row.  Each wave owns a contiguous segment of the row and,
 // when the segment fits NK values per lane, keeps its keys in registers: the scores are then read
 // from memory once for the four digit passes, the count and the ordered emission.
-// The digit histogram is kept in SUB interleaved copies: lane l adds into copy l % SUB, which lies in a
-// bank of its own, so that lanes of a wave with equal digits do not serialise on one LDS word.
+// The digit histogram is kept in SUB interleaved copies: lane l adds into copy l % SUB, so that lanes of a
+// wave with equal digits do not all serialise on one LDS word.
 // HIT = false: emits the kept positions into the cache (and idx_out).  HIT = true (Def. 3.1): `scores` are the
 // decode-query attention, the top-k set S* is found the same way with the cache's own budget and no
 // recent window, and instead of emitting it the block counts how many positions the cache already holds
@@ -303,7 +303,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
                                                              int32_t* __restrict__ hits_out, float* __restrict__ rate_out,
                                                              LayoutArgs la) {
     static_assert(!(HIT && FOLD), "the hit count reads a cache that is already laid out");
-    constexpr int kSelSub = NK == 8 ? 4 : 16;                  // short rows: few adds, the clear and the sum dominate
+    // copies of the histogram: short rows have few adds, so the clear and the sum dominate (4); long rows measured
+    // on the 7B shape with m = 10368: 4 copies 47.5 us, 8: 44.1, 16: 68.5, 32: 94.7 (with more copies the bank of an
+    // add depends less on its digit, and the lanes of a wave crowd into fewer banks)
+    constexpr int kSelSub = NK == 8 ? 4 : 8;
     __shared__ __align__(16) uint32_t hist[256 * kSelSub];
     __shared__ uint32_t sel_bin, sel_above;
     __shared__ uint32_t cnt_gt[kSelWaves], cnt_eq[kSelWaves];
@@ -413,15 +416,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __rest
             if (wave == 0) {
                 // lane i owns bins 4i..4i+3; find the highest bin whose count, added to everything
                 // above it, reaches `remaining`
-                uint32_t c[4];
+                uint32_t c[4] = {0, 0, 0, 0};
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    c[x] = 0;
+                for (int q = 0; q < kSelSub; ++q) {              // the lane's 4 bins x kSelSub copies are 4 kSelSub consecutive words
+                    const uint4 h4 = reinterpret_cast<const uint4*>(hist)[lane * kSelSub + q];
+                    const uint32_t w[4] = {h4.x, h4.y, h4.z, h4.w};
 #pragma unroll
-                    for (int q = 0; q < kSelSub / 4; ++q) {
-                        const uint4 h4 = reinterpret_cast<const uint4*>(hist)[(lane * 4 + x) * (kSelSub / 4) + q];
-                        c[x] += h4.x + h4.y + h4.z + h4.w;
-                    }
+                    for (int y = 0; y < 4; ++y) c[(q * 4 + y) / kSelSub] += w[y];
                 }
                 const uint32_t tot = c[0] + c[1] + c[2] + c[3];
                 uint32_t suf = tot;             // inclusive suffix sum over lanes >= this one
