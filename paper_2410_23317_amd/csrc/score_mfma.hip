@@ -146,8 +146,18 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     const int k_begin = split * a.keys_per_split;
     const int k_end = min(mb, k_begin + a.keys_per_split);
 
-    // the first K chunk is requested before anything else: the prologue below (Q' fragments, then the merge of
-    // sweep 1's partials with its barrier) runs while it is on its way
+    // Order of the first requests: the few bytes of sweep 1's partial statistics go out first (every block of the
+    // launch starts at once, and behind 32 KB of K per block they would wait for the whole burst), then the first
+    // K chunk, then the Q' fragments; the merge of the statistics and its barrier run while K is on its way.
+    constexpr int kSplitRegs = 4;               // splits whose partials a thread holds at once (more are merged in rounds)
+    float2 pin[kSplitRegs];
+    const int r_mine = a.rb0 * 32 + (int)threadIdx.x;       // the row whose statistics this thread merges (first round)
+    const bool mine = a.part_in && (int)threadIdx.x < WAVES * RB * 32 && r_mine < a.RP;
+    if (mine) {
+#pragma unroll
+        for (int sp = 0; sp < kSplitRegs; ++sp)
+            pin[sp] = sp < a.nsplit ? a.part_in[((size_t)group * a.nsplit + sp) * a.RP + r_mine] : make_float2(-INFINITY, 0.f);
+    }
     KStage<THREADS> st;
     if (k_begin < k_end) st.load(kg, k_begin, mb);
     uint4 qf[RB][kKSteps];
@@ -164,12 +174,23 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
             float2 st = make_float2(INFINITY, 0.f);
             const int hl = r / a.tauP, iw = r % a.tauP;
             if (r < a.RP && hl < a.g && iw < tb) {
-                float M = -INFINITY;
-                for (int sp = 0; sp < a.nsplit; ++sp) M = fmaxf(M, a.part_in[((size_t)group * a.nsplit + sp) * a.RP + r].x);
-                float Z = 0.f;
-                for (int sp = 0; sp < a.nsplit; ++sp) {
-                    const float2 pp = a.part_in[((size_t)group * a.nsplit + sp) * a.RP + r];
-                    if (pp.x > -INFINITY) Z += pp.y * exp2_fast(pp.x - M);
+                float M = -INFINITY, Z = 0.f;
+                for (int sp0 = 0; sp0 < a.nsplit; sp0 += kSplitRegs) {
+                    if (sp0 > 0 || t != (int)threadIdx.x) {          // beyond what was requested at the start
+#pragma unroll
+                        for (int sp = 0; sp < kSplitRegs; ++sp)
+                            pin[sp] = sp0 + sp < a.nsplit ? a.part_in[((size_t)group * a.nsplit + sp0 + sp) * a.RP + r] : make_float2(-INFINITY, 0.f);
+                    }
+                    float Mn = M;
+#pragma unroll
+                    for (int sp = 0; sp < kSplitRegs; ++sp) Mn = fmaxf(Mn, pin[sp].x);
+                    if (Mn > -INFINITY) {
+                        Z *= exp2_fast(M - Mn);                       // 0 on the first round (M = -inf)
+#pragma unroll
+                        for (int sp = 0; sp < kSplitRegs; ++sp)
+                            if (pin[sp].x > -INFINITY) Z += pin[sp].y * exp2_fast(pin[sp].x - Mn);
+                        M = Mn;
+                    }
                 }
                 st = make_float2(M, 1.f / Z);
                 if (split == 0) {                  // either output may be absent (a count-only sweep keeps no row sums)
@@ -208,7 +229,9 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 3 : 4) void colsweep_mfma_
     }
 
     for (int kc = k_begin; kc < k_end; kc += kChunk) {
-        __syncthreads();
+        // no barrier in front of the store: the one that follows the tiles of the previous chunk (below) already
+        // orders every wave's reads of sK before it, and the readers of sCol pass the barrier after the store
+        // before any wave writes sCol again
         st.store(sK);
         __syncthreads();
         if (kc + kChunk < k_end) st.load(kg, kc + kChunk, mb);
