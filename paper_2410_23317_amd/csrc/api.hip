@@ -327,18 +327,15 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     //   rows >= 4 x the resident blocks: 2048-slot units (most rows are one unit: no partials at all);
     //   rows >= 1.3 x: the power of two above the mean row, so that an average row is one unit;
     //   fewer rows: 512-slot units for long rows, 256 for short ones, so that the chip still fills.
-    // The longest-first order exists for up to kLayoutSortMax (request, layer) entries; beyond, the last rule.
     if (!o.unit_slots) {
         const int64_t rows = (int64_t)BL * s->Hkv;
         const int g = s->Hq / s->Hkv;
         const int64_t resident = 256 * ((g <= 4 && (s->dtype != VLC_F32 || s->d == 64)) ? 3 : 2);
         int u = mean_row >= 768 ? 512 : 256;
-        if (BL <= (size_t)vlc::kLayoutSortMax) {
-            if (rows >= 4 * resident) u = 2048;
-            else if (rows * 10 >= resident * 13) {
-                u = 256;
-                while (u < mean_row && u < 2048) u <<= 1;
-            }
+        if (rows >= 4 * resident) u = vlc::kMaxUnitSlots;
+        else if (rows * 10 >= resident * 13) {
+            u = 256;
+            while (u < mean_row && u < vlc::kMaxUnitSlots) u <<= 1;
         }
         o.unit_slots = u;
         if (o.tail_unit_slots > o.unit_slots) o.unit_slots = o.tail_unit_slots;

@@ -40,7 +40,7 @@ struct WorkItem {
 };
 static_assert(sizeof(WorkItem) == 64, "WorkItem layout: one 64-byte scalar load");
 
-constexpr int kLayoutSortMax = 512;    // up to this many (request, layer) entries the size-class list has its partly filled units longest first
+constexpr int kMaxUnitSlots = 2048;     // largest block-unit of a work list (the options admit 128 .. 2048)
 constexpr int kNumLists = 3;
 constexpr int kGatherUnit = 256;        // slots per unit of the gather's list
 

@@ -52,7 +52,7 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
     __shared__ int32_t sBigFirst[kLayoutMaxBL], sLiveFirst[kLayoutMaxBL], sResFirst[kLayoutMaxBL];
     __shared__ int sTotals[2];
     __shared__ int sBad;
-    __shared__ int16_t sPerm[kLayoutSortMax];      // (request, layer) entries in the order of the size-class walk's second class
+    __shared__ uint32_t sSort[kLayoutMaxBL];        // (request, layer) entries in the order of the size-class walk's second class
     const int tid = threadIdx.x;
     const int BL = B * L;
     const bool first = part == 0;               // the part that owns everything but the lists of part 1
@@ -163,25 +163,38 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
         if (sBad) return;
         // Size-class order, second class (the units that are partly filled): longest first, so that the blocks
         // dispatched last, which decide when the launch ends, are the shortest.  All rows of a (request, layer) entry
-        // have the same fill, so the entries are ranked (by the slots their rows hold beyond whole u_big units,
-        // descending, ties in list order: a count over all entries, cheap while there are few) and the class's
-        // positions are the prefix sums in that order.  With more entries the class keeps the list order.
-        if (wl.by_size && BL <= kLayoutSortMax) {
-            for (int y = tid; y < BL; y += NT) {
-                const int kk = sKept[(y % B) * L + y / B], key = kk - (kk / ub) * ub;
-                int rank = 0;
-                for (int z = 0; z < BL; ++z) {
-                    const int kz = sKept[(z % B) * L + z / B], keyz = kz - (kz / ub) * ub;
-                    rank += (keyz > key || (keyz == key && z < y)) ? 1 : 0;
+        // have the same fill, so the entries are sorted (by the slots their rows hold beyond whole u_big units,
+        // descending, ties in list order: a bitonic sort in LDS of one word per entry, u_big - 1 - fill above the
+        // entry's list position) and the class's positions are the prefix sums in that order.
+        if (wl.by_size) {
+            static_assert(kLayoutMaxBL <= 2048 && kMaxUnitSlots <= 2048, "11 bits each for the fill and the entry");
+            int n2 = 1;
+            while (n2 < BL) n2 <<= 1;
+            for (int y = tid; y < n2; y += NT) {
+                uint32_t v = 0xffffffffu;                       // padding sorts last
+                if (y < BL) {
+                    const int kk = sKept[(y % B) * L + y / B];
+                    v = ((uint32_t)(ub - 1 - (kk - (kk / ub) * ub)) << 11) | (uint32_t)y;
                 }
-                sPerm[rank] = (int16_t)y;
+                sSort[y] = v;
             }
             __syncthreads();
+            for (int kb = 2; kb <= n2; kb <<= 1)
+                for (int j = kb >> 1; j > 0; j >>= 1) {
+                    for (int x = tid; x < n2; x += NT) {
+                        const int p = x ^ j;
+                        if (p > x) {
+                            const uint32_t va = sSort[x], vb = sSort[p];
+                            if ((va > vb) == ((x & kb) == 0)) { sSort[x] = vb; sSort[p] = va; }
+                        }
+                    }
+                    __syncthreads();
+                }
             const int per2 = (BL + NT - 1) / NT;
             const int r0 = tid * per2, r1 = min(BL, r0 + per2);
             int runl = 0;
             for (int r = r0; r < r1; ++r) {
-                const int y = sPerm[r];
+                const int y = (int)(sSort[r] & 2047u);
                 runl += row_units(sKept[(y % B) * L + y / B], T_max, ub, us).live * Hkv;
             }
             int incl = runl;
@@ -196,7 +209,7 @@ __device__ void layout_body(const LayoutArgs& a, CacheDev dev, int part) {
                 if (w < wv) incl += (int)sScan[w];
             int accl = incl - runl;
             for (int r = r0; r < r1; ++r) {
-                const int y = sPerm[r], bl = (y % B) * L + y / B;
+                const int y = (int)(sSort[r] & 2047u), bl = (y % B) * L + y / B;
                 sLiveFirst[bl] = accl;
                 accl += row_units(sKept[bl], T_max, ub, us).live * Hkv;
             }
