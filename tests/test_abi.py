@@ -150,6 +150,25 @@ def test_cache_options_are_validated_and_reported(V):
     assert V.lib.vlc_cache_create_opt(C.byref(f32), 8, 120, C.byref(o), 4096, 1 << 30, C.byref(h)) == V.VLC_ERR_DTYPE
 
 
+def test_default_unit_sizes_of_the_benchmark_shapes(V):
+    """The library's own choice of block-unit sizes (all-layer list, its tail units, per-layer list) for the four
+    benchmark shapes at a 10 % budget and 100 decode steps: few rows keep small units so that the chip fills, many
+    rows get units that hold a whole average row."""
+    import workloads as W
+    lay = V.vlc_cache_layout()
+    h = C.c_void_p()
+    want = {1: (256, 256, 128), 2: (2048, 2048, 256), 3: (2048, 2048, 256), 4: (512, 512, 256)}
+    for cid, units in want.items():
+        cfg = W.CONFIGS[cid]
+        s = V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
+        sum_k = cfg.L * cfg.m // 10 + cfg.L * (cfg.m // 100 + 1)
+        n = V.vlc_cache_bytes(s, 100, sum_k)
+        assert V.lib.vlc_cache_create(C.byref(s), 100, sum_k, 4096, n, C.byref(h)) == V.VLC_OK
+        assert V.lib.vlc_cache_get_layout(h, C.byref(lay)) == V.VLC_OK
+        V.lib.vlc_cache_destroy(h)
+        assert (lay.unit_slots, lay.tail_unit_slots, lay.layer_unit_slots) == units, cid
+
+
 def test_shape_flags(V):
     s = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16")
     plain = V.make_shape(1, 2, 8, 2, 128, 3000, 32, "bf16", flags=V.VLC_SHAPE_SCORE_PLAIN_ALU)
