@@ -62,7 +62,7 @@ struct DecodeParams {
     int ub_shift, us_shift;  // log2 of the list's unit sizes
     int B, L, Hq, Hkv, m;
     int layer_begin, n_layers, T_max;
-    int append_mode;         // 0: attend only; 1: k_new / v_new are appended by this kernel; 2: they were stored by the append kernel of this call
+    int append_mode;         // 0: attend only; 1: k_new / v_new are appended by this kernel
     int merge_mode;          // 1: last unit of a row merges in-kernel; 2: separate merge kernel
     int zigzag;              // 1 off; 2: tile order within a unit alternates between steps; 3: also the walk over the whole units
     int kv_fp8;              // the cache rows are E4M3 codes with per-row scales
@@ -226,8 +226,8 @@ template <> struct IsBf16<bf16_t> { static constexpr bool value = true; };
 
 // Q8: the cache rows are E4M3 codes with one fp32 scale per row (8 bytes per lane instead of 16); codes are
 // expanded to bf16 (exactly) where they are consumed, the K scale multiplies the finished logit, the
-// V scale the probability before it is rounded to bf16.  Appends to such a cache are done by
-// append_fp8_kernel before this kernel runs.
+// V scale the probability before it is rounded to bf16.  The row being appended is quantised by the wave whose tile
+// holds its slot, which attends over the quantised row and stores it.
 // Blocks of four waves, three per CU for up to four query heads per KV head (two where the accumulators need the
 // registers): the blocks of a CU overlap each other's start-up and merge phases.  One wide block per row (12 waves,
 // no merge across blocks) measured no faster: the row's loads then queue at a single CU's address path.
@@ -631,10 +631,43 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
         const bool rev = A.zigzag > 1 && (step & 1);
         if (nt_w > 0) { const int t0 = tw0 + (rev ? nt_w - 1 : 0) * NW * TK; issue_k(t0); issue_v(t0); }
         const int ticket = take_ticket();
+        // FP8 cache, appending: the wave one of whose tiles holds the new slot quantises the new row (every 16-lane
+        // row group the same row, so each lane gets the codes of its 8 elements and the row's scale) while the loads of
+        // its first tile are on their way, and stores codes, scales and position into the cache.  In the tile that
+        // holds the slot it replaces what the loads brought for it (the loads make no exception for the slot: a test
+        // in their fast path cost 40 registers).
+        uint2 qk_new = make_uint2(0, 0), qv_new = make_uint2(0, 0);
+        float sk_new = 0.f, sv_new = 0.f;
+        if constexpr (Q8) {
+            if (new_slot >= key0 && new_slot < key0 + ucap && ((new_slot - key0) / TK) % NW == wave) {      // wave-uniform
+                qk_new = quantize_row_e4m3<LPR>(*reinterpret_cast<const uint4*>(knew + c * 8), sk_new);
+                qv_new = quantize_row_e4m3<LPR>(*reinterpret_cast<const uint4*>(vnew + c * 8), sv_new);
+                if (!(VLC_DECODE_ABLATE & 8) && sub == 0) {
+                    *reinterpret_cast<uint2*>(const_cast<uint8_t*>(K8) + (int64_t)new_slot * D + c * 8) = qk_new;
+                    *reinterpret_cast<uint2*>(const_cast<uint8_t*>(V8) + (int64_t)new_slot * D + c * 8) = qv_new;
+                    if (c == 0) {
+                        const_cast<float*>(Ksc)[new_slot] = sk_new;
+                        const_cast<float*>(Vsc)[new_slot] = sv_new;
+                        A.dev.idx[idx_base + new_slot] = A.m + appended;
+                    }
+                }
+            }
+        }
 #pragma unroll 1
         for (int i = 0; i < nt_w; ++i) {
             const int t0 = tw0 + (rev ? nt_w - 1 - i : i) * NW * TK;
             if (i > 0) { issue_k(t0); issue_v(t0); }
+            if constexpr (Q8) {
+                if (new_slot >= t0 && new_slot < t0 + TK) {         // wave-uniform: this is the wave that quantised the new row
+                    const int rel = new_slot - t0;
+#pragma unroll
+                    for (int j = 0; j < NIT; ++j)
+                        if (rel / KPI == j && rel % KPI == sub) { kb8[j] = qk_new; ksc[j] = sk_new; vb8[j] = qv_new; }
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk)
+                        if (t0 + scol + 16 * kk == new_slot) vsc[kk] = sv_new;
+                }
+            }
             const bool full = (t0 + TK <= len);
             if (full) tile_body(std::true_type{}, t0); else tile_body(std::false_type{}, t0);
         }
@@ -766,37 +799,6 @@ __global__ __launch_bounds__(256, (G <= 4 && (IsBf16<T>::value || D == 64) ? 3 :
     }
 }
 
-// Append to an FP8 cache: one wave per (layer, request, KV head) row quantises the new key and value
-// (lanes [0, LPR) the key, [LPR, 2 LPR) the value) into slot kept + appended and records its position.
-// The attention kernel that follows in the same call counts the step (append mode 2).
-template <int D>
-__global__ __launch_bounds__(64) void append_fp8_kernel(DecodeParams P) {
-    constexpr int LPR = D / 8;
-    const int row = blockIdx.x;
-    const int hkv = row % P.Hkv;
-    const int b = (row / P.Hkv) % P.B;
-    const int lr = row / (P.Hkv * P.B);
-    const int bl = b * P.L + P.layer_begin + lr;
-    const int kept = P.dev.kept[bl];
-    const int appended = P.dev.appended[P.layer_begin];
-    if (kept == 0 || appended >= P.T_max) return;      // rejected row; no slot left (the attention kernel reports it)
-    const int cap = kept + P.T_max;
-    const int64_t so = P.dev.slot_off[bl];
-    const int64_t kbase = ((so * 2 * P.Hkv) + (int64_t)hkv * cap) * D;
-    const int slot = kept + appended;
-    const int lane = threadIdx.x, c = lane % LPR, which = lane / LPR;         // which: 0 key, 1 value, others idle
-    const bf16_t* src = reinterpret_cast<const bf16_t*>(which == 1 ? P.v_new : P.k_new) +
-                        ((size_t)(lr * P.B + b) * P.Hkv + hkv) * D + c * 8;
-    float scale;
-    const uint2 q = quantize_row_e4m3<LPR>(*reinterpret_cast<const uint4*>(src), scale);
-    if (which < 2) {
-        const int64_t voff = which ? (int64_t)P.Hkv * cap : 0;                  // value rows follow the key rows of the slab
-        *reinterpret_cast<uint2*>(P.dev.kv + kbase + voff * D + (int64_t)slot * D + c * 8) = q;
-        if (c == 0) P.dev.scales[kbase / D + voff + slot] = scale;
-    }
-    if (lane == 0) P.dev.idx[so * P.Hkv + (int64_t)hkv * cap + slot] = P.m + appended;
-}
-
 // Second kernel of merge mode 2: one block per (layer, request, KV head) row.  It runs after the attention
 // kernel of the same call, so the append count it reads already includes this call's step.
 template <typename T, int D, int G>
@@ -883,13 +885,6 @@ hipError_t launch_decode(const DecodeArgs& a) {
     if (!all_layers && grid > 3 * (int64_t)c.num_cus) grid = 3 * (int64_t)c.num_cus;
     if (grid < 1) grid = 1;
     const int g = s.Hq / s.Hkv;
-    if (c.kv_fp8 && a.k_new) {
-        // the new rows are quantised into their slots first; the attention kernel then sees them as cached
-        if (s.d == 64) append_fp8_kernel<64><<<rows, 64, 0, a.stream>>>(P);
-        else append_fp8_kernel<128><<<rows, 64, 0, a.stream>>>(P);
-        P.k_new = nullptr; P.v_new = nullptr;
-        P.append_mode = 2;
-    }
     if (s.dtype == VLC_F32)
         return s.d == 64 ? launch_g<float, 64>(P, g, (int)grid, rows, a.stream) : launch_g<float, 128>(P, g, (int)grid, rows, a.stream);
     return s.d == 64 ? launch_g<bf16_t, 64>(P, g, (int)grid, rows, a.stream) : launch_g<bf16_t, 128>(P, g, (int)grid, rows, a.stream);
