@@ -240,7 +240,8 @@ vlc_status vlc_cache_create_fp8(const vlc_shape* shape, int32_t T_max, int64_t s
  *                     128 .. 2048, not above unit_slots
  *   layer_unit_slots  slots per unit for launches over a layer range (how a model calls decode): 128 .. 2048
  *   decode_order      1: launches over all layers walk the units layer by layer; 2: by size class (whole
- *                     units first, then row ends, then append reserve), so the blocks dispatched last are short
+ *                     units first, then row ends with the longest first, then append reserve), so the blocks
+ *                     dispatched last are short
  *   decode_merge      1: the unit of a row that finishes last merges the row's partial results inside the
  *                     decode kernel; 2: a second kernel merges
  *   decode_zigzag     1: off; 2: a wave walks its tiles backwards on odd steps; 3: also the whole units of a
