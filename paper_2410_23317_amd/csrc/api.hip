@@ -320,24 +320,35 @@ static vlc_status cache_layout(const vlc_shape* s, int32_t T_max, int64_t sum_k_
     const int64_t spr = sum_k_max + (int64_t)s->L * T_max;
     const int64_t mean_row = sum_k_max / s->L + T_max / 2;    // slots of an average row half-way through decode
     // ---- the library's own choices
-    // Launches over all layers (measured on the ragged budgets of the 7B and 34B shapes at batch 1 to 16, on an
+    // Launches over all layers (measured on the ragged budgets of the 7B and 34B shapes at batch 1 to 64, on an
     // MI355X: 256 CUs, three blocks of this kernel per CU, two when a KV head serves more than four query heads).
     // The walk is by size class with the partly filled units longest first, so balance comes from the order; what
     // the unit size trades is the cost of a unit's start, merge and cross-block chain against having enough units.
     //   rows >= 4 x the resident blocks: 2048-slot units (most rows are one unit: no partials at all);
-    //   rows >= 1.3 x: the power of two above the mean row, so that an average row is one unit;
-    //   fewer rows: 512-slot units for long rows, 256 for short ones, so that the chip still fills.
+    //   rows >= 1.3 x: the power of two above the mean row, so that an average row is one unit (at most 1024 slots
+    //     below 2.5 x when a KV head serves more than four query heads: 960 rows of the 34B shape lose 20 % with 2048);
+    //   fewer rows: whole units of the largest power of two below the slots per resident block (at least 512 slots
+    //     for long rows, 256 for short ones, so that the chip still fills), and the rest of a row in units of at most
+    //     512 slots, which the longest-first order then spreads behind the whole units.
     if (!o.unit_slots) {
         const int64_t rows = (int64_t)BL * s->Hkv;
         const int g = s->Hq / s->Hkv;
         const int64_t resident = 256 * ((g <= 4 && (s->dtype != VLC_F32 || s->d == 64)) ? 3 : 2);
-        int u = mean_row >= 768 ? 512 : 256;
-        if (rows >= 4 * resident) u = vlc::kMaxUnitSlots;
-        else if (rows * 10 >= resident * 13) {
+        int u, tail;
+        if (rows >= 4 * resident) {
+            u = tail = vlc::kMaxUnitSlots;
+        } else if (rows * 10 >= resident * 13) {
             u = 256;
             while (u < mean_row && u < vlc::kMaxUnitSlots) u <<= 1;
+            if (g > 4 && rows * 2 < resident * 5 && u > 1024) u = 1024;
+            tail = u;
+        } else {
+            u = mean_row >= 768 ? 512 : 256;
+            while ((int64_t)u * 2 * resident <= rows * mean_row && u < vlc::kMaxUnitSlots) u <<= 1;
+            tail = u < 512 ? u : 512;
         }
         o.unit_slots = u;
+        if (!o.tail_unit_slots) o.tail_unit_slots = tail;
         if (o.tail_unit_slots > o.unit_slots) o.unit_slots = o.tail_unit_slots;
     }
     if (!o.tail_unit_slots) o.tail_unit_slots = o.unit_slots;

@@ -157,7 +157,7 @@ def test_default_unit_sizes_of_the_benchmark_shapes(V):
     import workloads as W
     lay = V.vlc_cache_layout()
     h = C.c_void_p()
-    want = {1: (256, 256, 128), 2: (2048, 2048, 256), 3: (2048, 2048, 256), 4: (512, 512, 256)}
+    want = {1: (256, 256, 128), 2: (2048, 2048, 256), 3: (2048, 2048, 256), 4: (1024, 512, 256)}
     for cid, units in want.items():
         cfg = W.CONFIGS[cid]
         s = V.make_shape(cfg.B, cfg.L, cfg.Hq, cfg.Hkv, cfg.d, cfg.m, cfg.tau, cfg.dtype)
