@@ -32,8 +32,8 @@ MFMA_BF16_PEAK_FLOPS = 2.5e15
 # counter reads for a plain 256 MiB copy), measured offline on the default run of a config: 10 % budget,
 # 100 decode steps.  The figures and the commands are in profiles/all_kernels_cfg*.md; TRAFFIC_MEASURED_AT names
 # the commit whose decode kernel they were measured on (a test checks that the constants match the profiles).
-MEASURED_DECODE_TRAFFIC_MIB = {1: 45.15 + 1.21, 2: 546.09 + 2.14}
-TRAFFIC_MEASURED_AT = "bb50741"
+MEASURED_DECODE_TRAFFIC_MIB = {1: 45.15 + 1.21, 2: 546.11 + 2.14}
+TRAFFIC_MEASURED_AT = "dd0cd9f"
 
 
 def options_from_args(V, args):
