@@ -283,6 +283,20 @@ typedef struct {
     int32_t kv_fp8;        /* 1 if the rows are FP8 E4M3 codes */
     int32_t unit_slots, tail_unit_slots, layer_unit_slots;   /* the block-unit sizes in effect (see vlc_cache_options) */
     size_t appended_off;   /* int32[L]: appends each layer has received since the last compaction */
+    /* The work lists the kernels walk, written by vlc_topk_compact: list 0 for decode launches over a layer range,
+     * list 1 for decode launches over all layers, list 2 for the gather (it may be the same memory as list 0 or 1).
+     * A list is an array of 64-byte records, one per block-unit of a cached row:
+     *   int32 row ((b*L + l)*Hkv + kv head), first slot, kept (k[b][l]; 0 = rejected request), unit index in its row;
+     *   int64 K slab offset (elements), int64 kept-index offset; int32 b, l, position in (layer, request, kv head, unit)
+     *   order, slots of the unit, kv head, units of layer l in this list; 8 bytes of padding.
+     * list_index_off[i] points at int32[L+2]: the position of each layer's first unit in that order, then the number of
+     * units, then the number of whole unit_slots units.  With list_by_size[i] = 1 the records are stored by size class:
+     * the whole units, then the other units that hold kept rows ((request, layer) entries with the most slots beyond
+     * their whole units first), then the units that only hold append reserve; else in (layer, request, kv head, unit) order. */
+    size_t list_items_off[3];
+    size_t list_index_off[3];
+    int32_t list_by_size[3];
+    int32_t list_reserved;
 } vlc_cache_layout;
 vlc_status vlc_cache_get_layout(const vlc_cache* cache, vlc_cache_layout* out);
 

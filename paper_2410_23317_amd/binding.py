@@ -38,7 +38,9 @@ class vlc_cache_layout(C.Structure):
                 ("kv_off", C.c_size_t), ("idx_off", C.c_size_t), ("scratch_off", C.c_size_t),
                 ("total_bytes", C.c_size_t), ("slots_per_request", C.c_int64), ("scale_off", C.c_size_t),
                 ("kv_fp8", C.c_int32), ("unit_slots", C.c_int32), ("tail_unit_slots", C.c_int32),
-                ("layer_unit_slots", C.c_int32), ("appended_off", C.c_size_t)]
+                ("layer_unit_slots", C.c_int32), ("appended_off", C.c_size_t),
+                ("list_items_off", C.c_size_t * 3), ("list_index_off", C.c_size_t * 3),
+                ("list_by_size", C.c_int32 * 3), ("list_reserved", C.c_int32)]
 
 
 class vlc_cache_options(C.Structure):

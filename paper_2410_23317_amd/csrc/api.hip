@@ -465,6 +465,12 @@ static vlc_status cache_create_common(const char* who, const vlc_shape* shape, i
         const vlc::WorkList& wl = c->dev.list[i];
         if (wl.u_big == vlc::kGatherUnit && wl.u_small == vlc::kGatherUnit && !wl.by_size) c->dev.list[2] = wl;
     }
+    for (int i = 0; i < vlc::kNumLists; ++i) {
+        c->layout.list_items_off[i] = (size_t)((char*)c->dev.list[i].items - c->arena);
+        c->layout.list_index_off[i] = (size_t)((char*)c->dev.list[i].layer_start - c->arena);
+        c->layout.list_by_size[i] = c->dev.list[i].by_size;
+    }
+    c->layout.list_reserved = 0;
     c->dev.partials = (float*)(c->arena + plan.partials_off);
     c->dev.counters = (int32_t*)(c->arena + plan.counters_off);
     c->dev.readers = (int32_t*)(c->arena + plan.readers_off);

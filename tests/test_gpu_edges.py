@@ -486,6 +486,77 @@ def test_size_class_walk_with_budgets_of_every_length(B, L, m):
     path.status()
 
 
+_WORK_ITEM = np.dtype([("row", "<i4"), ("key0", "<i4"), ("kept", "<i4"), ("unit", "<i4"), ("kbase", "<i8"), ("idx_base", "<i8"),
+                       ("b", "<i4"), ("l", "<i4"), ("canon", "<i4"), ("ucap", "<i4"), ("hkv", "<i4"), ("layer_units", "<i4"),
+                       ("pad", "<i4", (2,))])
+
+
+def _read_list(path, i, L):
+    """Work list i of a cache as the layout struct describes it: (records, layer index int32[L+2])."""
+    lay = path.cache.layout
+    index = path.cache.arena[lay.list_index_off[i]: lay.list_index_off[i] + 4 * (L + 2)].view(torch.int32).cpu().numpy()
+    n = int(index[L])
+    raw = path.cache.arena[lay.list_items_off[i]: lay.list_items_off[i] + 64 * n].cpu().numpy()
+    return np.frombuffer(raw.tobytes(), dtype=_WORK_ITEM), index
+
+
+@pytest.mark.parametrize("unit,tail", [(128, 128), (256, 128), (512, 128)])
+def test_work_lists_hold_every_unit_once_and_the_size_classes_in_order(unit, tail):
+    """The lists the decode and gather kernels walk, read back from the arena: every block-unit of every row exactly
+    once in each list; the all-layer list by size class, i.e. first the whole units, then the other units that hold
+    kept slots with the (request, layer) entries in the order of their slots beyond whole units, longest first and
+    ties in (layer, request) order, then the units that only hold append reserve; the per-layer list in (layer,
+    request, kv head, unit) order with its layer index."""
+    assert _WORK_ITEM.itemsize == 64
+    V = _V()
+    B, L, Hkv, T = 5, 7, 2, 40
+    cfg = _small_cfg(cid=93, m=1600, n_visual=1500, L=L, B=B, Hq=4, Hkv=Hkv, d=64, tau=16)
+    rng = np.random.default_rng(93)
+    kk = rng.choice(np.array([1, 50, 127, 128, 129, 255, 256, 300, 384, 511, 512, 513, 640, 700, 767, 768]), size=(B, L))
+    path, dev, caches, scales = _direct_cache(V, cfg, kk, T, dict(unit_slots=unit, tail_unit_slots=tail, layer_unit_slots=128,
+                                                                   decode_order=2))
+    lay = path.cache.layout
+    assert list(lay.list_by_size) == [0, 1, 0]
+
+    def units_of(k, ub, us):                   # (first slot, slots of the unit) of every unit of a row with k kept slots
+        big, rem = k // ub, k % ub
+        small = -(-(rem + T) // us)
+        return [(u * ub, ub) for u in range(big)] + [(big * ub + u * us, us) for u in range(small)]
+
+    for i, (ub, us) in enumerate([(128, 128), (unit, tail), (256, 256)]):
+        items, index = _read_list(path, i, L)
+        want = {}
+        for l in range(L):                                        # the order the position field counts in
+            for b in range(B):
+                for h in range(Hkv):
+                    for u, (k0, cap) in enumerate(units_of(int(kk[b, l]), ub, us)):
+                        want[((b * L + l) * Hkv + h, u)] = (len(want), k0, cap, b, l, h)
+        assert len(items) == len(want), i
+        got = {(int(r["row"]), int(r["unit"])): r for r in items}
+        assert len(got) == len(items), f"list {i}: a unit is listed twice"
+        for key, (canon, k0, cap, b, l, h) in want.items():
+            r = got[key]
+            assert (r["canon"], r["key0"], r["ucap"], r["b"], r["l"], r["hkv"], r["kept"]) == (canon, k0, cap, b, l, h, kk[b, l]), (i, key)
+        firsts = [want[((0 * L + l) * Hkv + 0, 0)][0] for l in range(L)]
+        assert index[:L].tolist() == firsts and index[L] == len(want), i
+        if not lay.list_by_size[i]:
+            assert items["canon"].tolist() == list(range(len(items))), i
+            continue
+        # size classes: whole units | units with kept slots, entries by slots beyond whole units, longest first | reserve
+        whole = items["ucap"] == ub if ub != us else (items["key0"] + ub <= items["kept"])
+        whole &= items["key0"] + items["ucap"] <= items["kept"] - items["kept"] % ub
+        live = ~whole & (items["key0"] < items["kept"])
+        cls = np.where(whole, 0, np.where(live, 1, 2))
+        assert np.all(np.diff(cls) >= 0), "size classes out of order"
+        assert int(whole.sum()) == int(index[L + 1])
+        mid = items[cls == 1]
+        fill = mid["kept"] % ub
+        entry = mid["l"] * B + mid["b"]                           # ties keep the (layer, request) order
+        order = list(zip((-fill).tolist(), entry.tolist()))
+        assert order == sorted(order), "partly filled units are not longest first"
+    path.status()
+
+
 @pytest.mark.parametrize("fp8", [False, True], ids=["bf16-cache", "fp8-cache"])
 def test_launches_over_layer_ranges_that_are_neither_one_layer_nor_all(fp8):
     """A decode step issued as launches over parts of the layer stack: [0,2) + [2,4) on even steps, [0,1) + [1,4) on
