@@ -16,14 +16,15 @@ constexpr int kReaderStride = 64;      // ints between the ticket counters of tw
                                        // line cost a launch over all layers of the 7B shape 1.7 of 16 us)
 
 // One block-unit of decode work: consecutive cache slots [key0, key0 + ucap) of one (b, l, kv head) row.
-// vlc_topk_compact builds two lists of them on the device.  A row is cut into floor(kept / u_big) units of
+// vlc_topk_compact builds three lists of them on the device.  A row is cut into floor(kept / u_big) units of
 // u_big slots followed by units of u_small slots that hold the end of the row and the append reserve.
 //   list 0 (launches over a layer range): ordered by (layer, request, kv head, unit), so that a layer
 //           range is a contiguous slice;
 //   list 2 (the gather of the compaction): the same order, uniform fine units;
 //   list 1 (launches over all layers): the same order, or by size class (all u_big units, then the small
-//           units that hold kept rows, then the units that only hold append reserve), so that the blocks
-//           dispatched last are the short ones.
+//           units that hold kept rows, the (request, layer) entries with the most slots beyond their u_big
+//           units first, then the units that only hold append reserve), so that the blocks dispatched last
+//           are the short ones.
 struct WorkItem {
     int32_t row_abs;                   // (b*L + l)*Hkv + hkv
     int32_t key0;                      // first slot of the unit
