@@ -129,7 +129,8 @@ def run_and_check(cfg, alpha, n_steps, n_recent=0, layers_to_check=None, request
         k_o, beta_o = O.allocate(nnz[b], cfg.m, alpha[0], alpha[1])
         assert np.array_equal(kk[b], k_o), f"budgets of request {b} differ from Alg. 1 on the GPU's own counts"
         np.testing.assert_allclose(path.beta[b].cpu().numpy(), beta_o, rtol=1e-6)
-        quota_ok = (nnz[b].sum(1) * b_tot / nnz[b].sum() >= lo).all()
+        share = nnz[b].sum(1) * b_tot / nnz[b].sum()
+        quota_ok = (share >= lo).all() and (share <= cfg.m - 1).all()      # no clip binds (Alg. 1 does not renormalise)
         if quota_ok:
             assert int(kk[b].sum()) == b_tot
 
